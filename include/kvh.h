@@ -1,0 +1,155 @@
+/*
+ * kvh.h — C ABI of the MI355X KV-cache level codec.
+ *
+ * The operations are the two compute steps of the AdaptCache executor (Design section: the
+ * executor "implements the compression decisions"; the estimator profiles the "decompression
+ * overhead"): compress a KV-cache entry with the quantisation method at a chosen rate, and
+ * decompress a stored entry when it is loaded for reuse.  A KV-cache entry is a tensor of
+ * l layers x N tokens x c channels for each of K and V (the paper's NumLayers, NumTokens,
+ * NumChannels) stored at a quality level k (its Level); the only rate the paper names is
+ * "2 bits" (Preliminary Results).  The paper fixes no equations or formats for the codec; the
+ * concrete definition implemented here is:
+ *
+ *   level 0/1/2 -> b = 8/4/2 bits per element, L = 2^b - 1
+ *   K groups: 128 consecutive tokens of one channel; V groups: 128 consecutive channels of one
+ *   token.  Per group: mn/mx = min/max (stored as raw 16-bit values, -0 as +0),
+ *   r = f32(mx) - f32(mn); r < 2^-100 -> scale = inv = 0; else scale = r / L, inv = L / r;
+ *   code q = clamp(rne((f32(x) - f32(mn)) * inv), 0, L); codes of a token row are packed in
+ *   channel order, LSB-first; q == L decodes to mx, any other q to T16_rne(fma(q, scale, mn)).
+ *
+ * Blob (little-endian, position independent, movable with memcpy between storage tiers):
+ *   64-byte header { u32 magic 'KVH1'; u16 version = 1; u8 dtype; u8 bits; u32 l; u32 n; u32 c;
+ *                    u16 k_group = 128; u16 v_group = 128; u64 total_bytes; zero padding }
+ *   then for each layer:  kmeta[ceil(n/128)][c]{mn,mx}  kcodes[n][c*b/8]
+ *                         vmeta[n][c/128]{mn,mx}        vcodes[n][c*b/8]
+ *   each section padded with zero bytes to a multiple of 16.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; everything else is host
+ *     memory.  The library allocates nothing, keeps no state, and frees nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     ENQUEUES kernels and returns; results are valid once the caller has synchronised the
+ *     stream.  Device buffers must stay alive until then.
+ *   - Return value: KVH_OK or a negative kvh_status.  All argument errors are found on the host
+ *     before anything is launched; on error nothing is enqueued.
+ *   - Inputs must be finite.  Non-finite values give unspecified codes (never an out-of-bounds
+ *     access).
+ *   - Requirements: c a multiple of 128; blob bases 16-byte aligned; K/V bases 16-byte aligned
+ *     and strides multiples of 8 elements (so every row segment is 16-byte aligned); channel
+ *     stride 1.
+ */
+#ifndef KVH_H_
+#define KVH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { KVH_F16 = 0, KVH_BF16 = 1 } kvh_dtype;
+
+typedef enum {
+  KVH_OK = 0,
+  KVH_E_ARG = -1,   /* null pointer, bad dtype, negative offset, bad block_tokens, too many items */
+  KVH_E_LEVEL = -2, /* level outside 0..2 */
+  KVH_E_SHAPE = -3, /* l < 1, n < 1, c not a positive multiple of 128, chunk not a multiple of 128 */
+  KVH_E_SIZE = -4,  /* blob capacity too small */
+  KVH_E_ALIGN = -5, /* a base pointer or stride breaks the 16-byte rule */
+  KVH_E_HIP = -6    /* the kernel launch itself failed */
+} kvh_status;
+
+/* Value written to *status_dev by a decode kernel whose blob header disagrees with the call. */
+#define KVH_DEV_HEADER_MISMATCH 1
+
+/* The level table (reading of the paper's Level k / "compression rate"): 3 levels. */
+int kvh_num_levels(void);
+/* Bits per element of a level: 0,1,2 -> 8,4,2; anything else -> -1. */
+int kvh_level_bits(int level);
+/* Exact size in bytes of a blob holding n_tokens tokens; 0 on bad arguments.  This is the
+ * size(i, M_i, R_i) term of the paper's utility for the quantisation method. */
+size_t kvh_blob_size(int l, int n_tokens, int c, int level);
+
+/* A K/V tensor pair in device memory.  Host struct; k and v are device pointers to 16-bit
+ * elements.  Contiguous use: element (layer, token, ch) of K is k[layer*layer_stride +
+ * token*token_stride + ch].  Paged use (decode only): the tensors are [l][P][block_tokens][c],
+ * token_stride is the stride between slots of a block (normally c) and blocks are dense:
+ * physical row = block * block_tokens + slot.  Strides are in elements. */
+typedef struct {
+  void* k;
+  void* v;
+  int64_t layer_stride;
+  int64_t token_stride;
+} kvh_kv_view;
+
+/* Compress: encode tokens [0, N) of `kv` (all l layers, K and V) into ONE blob at `level`.
+ * blob_cap must be >= kvh_blob_size(l, N, c, level).  The last K token-group may be partial. */
+int kvh_encode(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int level, void* blob_dev, size_t blob_cap,
+               void* stream);
+
+/* Compress a long entry chunk by chunk (chunks are independently decodable): chunk i covers
+ * tokens [i*chunk, min(N, (i+1)*chunk)), is encoded at levels[i] and written at
+ * (char*)blobs_dev + blob_offsets[i].  `levels` and `blob_offsets` are HOST arrays of
+ * ceil(N/chunk) entries; offsets must be multiples of 16 and every blob must end at or before
+ * `cap`.  chunk must be a multiple of 128.  One kernel launch per chunk, all asynchronous on
+ * `stream`. */
+int kvh_encode_chunked(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int chunk, const int8_t* levels,
+                       void* blobs_dev, const size_t* blob_offsets, size_t cap, void* stream);
+
+/* One encode job of a batch.  The ARRAY of items lives in device memory. */
+typedef struct {
+  void* blob;         /* device pointer, 16-byte aligned, room for kvh_blob_size(l, n_tokens, c, level) */
+  int64_t src_token0; /* first token of the source view covered by this blob */
+  int32_t n_tokens;   /* 1 .. max_tokens_per_item */
+  int32_t level;      /* 0 .. 2 */
+} kvh_enc_item;
+
+/* Compress many chunks of one source view in ONE launch.  The host cannot see the items, so
+ * the caller guarantees their validity (levels in range, blobs large enough and disjoint,
+ * source rows inside the view); items with n_tokens < 1 or a bad level are skipped by the
+ * kernel.  n_items <= 65535. */
+int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                     const kvh_kv_view* src, void* stream);
+
+/* Decompress one blob of n_tokens tokens stored at `level` (the caller's index knows the
+ * method and rate of every entry — the (M_i, R_i) of the paper's utility) into `dst`:
+ *   page_table_dev == NULL: token t goes to row dst_token0 + t of the contiguous view;
+ *   otherwise: logical position s = dst_token0 + t goes to physical block
+ *              page_table_dev[s / block_tokens], slot s % block_tokens (one table for all layers
+ *              and for K and V).
+ * The kernel first compares the blob header with (dt, l, n_tokens, c, level); on disagreement it
+ * writes KVH_DEV_HEADER_MISMATCH to *status_dev (if not NULL) and writes nothing else.  The
+ * caller zeroes *status_dev beforehand; it is never written on success. */
+int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, int level, const kvh_kv_view* dst,
+               int64_t dst_token0, const int32_t* page_table_dev, int block_tokens, int32_t* status_dev, void* stream);
+
+/* One decode job of a batch.  The ARRAY of items lives in device memory. */
+typedef struct {
+  const void* blob;          /* device pointer, 16-byte aligned */
+  int32_t n_tokens;          /* 1 .. max_tokens_per_item */
+  int32_t level;             /* level the blob was stored at */
+  int64_t dst_token0;        /* logical position of the blob's first token in its request */
+  const int32_t* page_table; /* device pointer to the request's table, or NULL for contiguous */
+} kvh_item;
+
+/* Decompress many blobs (mixed levels, mixed lengths) into one destination view in ONE launch.
+ * status_dev, if not NULL, is an int32 array of n_items entries (zeroed by the caller); entry i
+ * is set to KVH_DEV_HEADER_MISMATCH when item i's header disagrees, and that item writes
+ * nothing.  Items whose n_tokens < 1 or level is out of range are skipped the same way.
+ * Destinations of different items must not overlap.  n_items <= 65535. */
+int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                     const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
+ * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that
+ * scales the HBM byte counters and as the practical copy-bandwidth ceiling of the device. */
+int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
+/* Static description of a status code. */
+const char* kvh_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVH_H_ */

@@ -1,0 +1,11 @@
+"""MI355X-native KV-cache level codec (kvh): thin ctypes binding over libkvh.so.
+
+Every step of the path (statistics, quantisation, bit-packing, unpacking, dequantisation,
+paged scatter) runs in the HIP kernels behind the C ABI of include/kvh.h; this package only
+marshals arguments.  torch is used for device memory and streams.  There is no CPU fallback:
+importing the binding without a built library raises.
+"""
+from .binding import (  # noqa: F401
+    BF16, F16, KVHError, blob_size, copy_probe, decode, decode_batch, encode, encode_batch, encode_chunked,
+    level_bits, lib, make_dec_items, make_enc_items, num_levels, strerror,
+)

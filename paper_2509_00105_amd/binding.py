@@ -1,0 +1,216 @@
+"""ctypes binding of the C ABI in include/kvh.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libkvh.so")
+
+F16, BF16 = 0, 1
+_TORCH_DT = {torch.float16: F16, torch.bfloat16: BF16}
+
+
+class KVHError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, strerror(status)))
+
+
+class _KVView(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("layer_stride", ctypes.c_int64), ("token_stride", ctypes.c_int64)]
+
+
+# Device-resident job descriptors, built as structured numpy arrays and uploaded by the caller.
+ENC_ITEM = np.dtype([("blob", "<u8"), ("src_token0", "<i8"), ("n_tokens", "<i4"), ("level", "<i4")], align=True)
+DEC_ITEM = np.dtype([("blob", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"),
+                     ("page_table", "<u8")], align=True)
+assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libkvh.so (built in-tree by `python -m paper_2509_00105_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libkvh.so is not built: run `python -m paper_2509_00105_amd.build` "
+                              "(there is no CPU fallback for the HIP path)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+        view = ctypes.POINTER(_KVView)
+        L.kvh_num_levels.restype = i32
+        L.kvh_num_levels.argtypes = []
+        L.kvh_level_bits.restype = i32
+        L.kvh_level_bits.argtypes = [i32]
+        L.kvh_blob_size.restype = sz
+        L.kvh_blob_size.argtypes = [i32, i32, i32, i32]
+        L.kvh_encode.restype = i32
+        L.kvh_encode.argtypes = [view, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.kvh_encode_chunked.restype = i32
+        L.kvh_encode_chunked.argtypes = [view, i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int8), vp,
+                                         ctypes.POINTER(sz), sz, vp]
+        L.kvh_encode_batch.restype = i32
+        L.kvh_encode_batch.argtypes = [vp, i32, i32, i32, i32, i32, view, vp]
+        L.kvh_decode.restype = i32
+        L.kvh_decode.argtypes = [vp, i32, i32, i32, i32, i32, view, i64, vp, i32, vp, vp]
+        L.kvh_decode_batch.restype = i32
+        L.kvh_decode_batch.argtypes = [vp, i32, i32, i32, i32, i32, view, i32, vp, vp]
+        L.kvh_copy_probe.restype = i32
+        L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.kvh_strerror.restype = ctypes.c_char_p
+        L.kvh_strerror.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().kvh_strerror(status).decode()
+
+
+def num_levels() -> int:
+    return lib().kvh_num_levels()
+
+
+def level_bits(level: int) -> int:
+    return lib().kvh_level_bits(level)
+
+
+def blob_size(l: int, n_tokens: int, c: int, level: int) -> int:
+    return lib().kvh_blob_size(l, n_tokens, c, level)
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if t is not None and not t.is_cuda:
+            raise ValueError("device tensor expected (the HIP path has no CPU fallback)")
+
+
+def _view(k: torch.Tensor, v: torch.Tensor, paged: bool = False):
+    """kvh_kv_view of K/V tensors [l][tokens][c] (or [l][P][block][c] when paged)."""
+    _require_cuda(k, v)
+    if k.dtype not in _TORCH_DT or v.dtype != k.dtype:
+        raise ValueError("K and V must both be float16 or both bfloat16")
+    want = 4 if paged else 3
+    if k.dim() != want or v.dim() != want or k.stride() != v.stride() or k.shape != v.shape:
+        raise ValueError("K and V must be %d-d with equal shapes and strides" % want)
+    if k.stride(-1) != 1:
+        raise ValueError("channel stride must be 1")
+    if paged and k.stride(1) != k.stride(2) * k.shape[2]:
+        raise ValueError("blocks of a paged cache must be densely packed")
+    ts = k.stride(2) if paged else k.stride(1)
+    return _KVView(k.data_ptr(), v.data_ptr(), k.stride(0), ts), _TORCH_DT[k.dtype]
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise KVHError(rc, where)
+
+
+def encode(k: torch.Tensor, v: torch.Tensor, level: int, blob: torch.Tensor | None = None, n_tokens: int | None = None,
+           stream=None) -> torch.Tensor:
+    """kvh_encode: tokens [0, n_tokens) of K/V [l][N][c] -> one blob (uint8 device tensor)."""
+    view, dt = _view(k, v)
+    l, N, c = k.shape
+    n = N if n_tokens is None else n_tokens
+    if blob is None:
+        size = blob_size(l, n, c, level)
+        if size == 0:
+            _check(lib().kvh_encode(ctypes.byref(view), dt, l, n, c, level, None, 0, None), "kvh_encode")
+        blob = torch.empty(size, dtype=torch.uint8, device=k.device)
+    _require_cuda(blob)
+    _check(lib().kvh_encode(ctypes.byref(view), dt, l, n, c, level, blob.data_ptr(), blob.numel(), _stream_ptr(stream)),
+           "kvh_encode")
+    return blob
+
+
+def encode_chunked(k: torch.Tensor, v: torch.Tensor, chunk: int, levels, blobs: torch.Tensor, blob_offsets,
+                   stream=None) -> None:
+    """kvh_encode_chunked: one launch per chunk, blobs written at the given byte offsets of `blobs`."""
+    view, dt = _view(k, v)
+    _require_cuda(blobs)
+    l, N, c = k.shape
+    lv = np.ascontiguousarray(levels, dtype=np.int8)
+    off = np.ascontiguousarray(blob_offsets, dtype=np.uint64)
+    n_chunks = -(-N // chunk) if chunk > 0 else 0
+    if lv.size != n_chunks or off.size != n_chunks:
+        raise ValueError("levels and blob_offsets need ceil(N/chunk) entries")
+    _check(lib().kvh_encode_chunked(ctypes.byref(view), dt, l, N, c, chunk,
+                                    lv.ctypes.data_as(ctypes.POINTER(ctypes.c_int8)), blobs.data_ptr(),
+                                    off.ctypes.data_as(ctypes.POINTER(ctypes.c_size_t)), blobs.numel(),
+                                    _stream_ptr(stream)), "kvh_encode_chunked")
+
+
+def make_enc_items(blob_ptrs, src_token0, n_tokens, levels, device) -> torch.Tensor:
+    """Upload an array of kvh_enc_item (argument marshalling; returns a uint8 device tensor)."""
+    a = np.zeros(len(blob_ptrs), dtype=ENC_ITEM)
+    a["blob"], a["src_token0"], a["n_tokens"], a["level"] = blob_ptrs, src_token0, n_tokens, levels
+    return torch.from_numpy(a.view(np.uint8).copy()).to(device)
+
+
+def make_dec_items(blob_ptrs, n_tokens, levels, dst_token0, page_table_ptrs, device) -> torch.Tensor:
+    """Upload an array of kvh_item (argument marshalling; returns a uint8 device tensor)."""
+    a = np.zeros(len(blob_ptrs), dtype=DEC_ITEM)
+    a["blob"], a["n_tokens"], a["level"], a["dst_token0"], a["page_table"] = \
+        blob_ptrs, n_tokens, levels, dst_token0, page_table_ptrs
+    return torch.from_numpy(a.view(np.uint8).copy()).to(device)
+
+
+def encode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, k: torch.Tensor, v: torch.Tensor,
+                 stream=None) -> None:
+    """kvh_encode_batch: all items in one launch; `items` comes from make_enc_items."""
+    view, dt = _view(k, v)
+    _require_cuda(items)
+    l, _, c = k.shape
+    _check(lib().kvh_encode_batch(items.data_ptr(), n_items, max_tokens_per_item, dt, l, c, ctypes.byref(view),
+                                  _stream_ptr(stream)), "kvh_encode_batch")
+
+
+def decode(blob: torch.Tensor, level: int, n_tokens: int, k_dst: torch.Tensor, v_dst: torch.Tensor, dst_token0: int = 0,
+           page_table: torch.Tensor | None = None, block_tokens: int = 16, status: torch.Tensor | None = None,
+           stream=None) -> None:
+    """kvh_decode: one blob -> rows of a contiguous [l][N][c] or paged [l][P][block][c] destination."""
+    paged = page_table is not None
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(blob, page_table, status)
+    if paged and page_table.dtype != torch.int32:
+        raise ValueError("page_table must be int32")
+    if status is not None and status.dtype != torch.int32:
+        raise ValueError("status must be int32")
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_decode(blob.data_ptr(), dt, l, n_tokens, c, level, ctypes.byref(view), dst_token0,
+                            page_table.data_ptr() if paged else None, block_tokens,
+                            status.data_ptr() if status is not None else None, _stream_ptr(stream)), "kvh_decode")
+
+
+def decode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, k_dst: torch.Tensor,
+                 v_dst: torch.Tensor, paged: bool = False, block_tokens: int = 16,
+                 status: torch.Tensor | None = None, stream=None) -> None:
+    """kvh_decode_batch: all items in one launch; `items` comes from make_dec_items."""
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(items, status)
+    if status is not None and (status.dtype != torch.int32 or status.numel() < n_items):
+        raise ValueError("status must be int32 with one entry per item")
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_decode_batch(items.data_ptr(), n_items, max_tokens_per_item, dt, l, c, ctypes.byref(view),
+                                  block_tokens, status.data_ptr() if status is not None else None,
+                                  _stream_ptr(stream)), "kvh_decode_batch")
+
+
+def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """kvh_copy_probe: plain copy kernel used to calibrate counters and the copy-bandwidth ceiling."""
+    _require_cuda(dst, src)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("destination too small")
+    _check(lib().kvh_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)), "kvh_copy_probe")

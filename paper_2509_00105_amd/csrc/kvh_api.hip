@@ -1,0 +1,193 @@
+// The extern "C" boundary declared in include/kvh.h: argument validation on the host, then
+// kernel launches on the caller's stream.  No allocation, no state, no synchronisation.
+#include "kvh_common.hpp"
+
+namespace kvh {
+
+namespace {
+
+constexpr int kMaxItems = 65535;   // gridDim.z
+constexpr int kMaxLayers = 32767;  // gridDim.y = 2 * l
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int l, int n, int c) {
+  if (l < 1 || l > kMaxLayers || n < 1 || c < kGroup || c % kGroup != 0) return KVH_E_SHAPE;
+  return KVH_OK;
+}
+
+int check_view(const kvh_kv_view* v) {
+  if (v == nullptr || v->k == nullptr || v->v == nullptr) return KVH_E_ARG;
+  if (v->layer_stride < 0 || v->token_stride < 0) return KVH_E_ARG;
+  if (!aligned16(v->k) || !aligned16(v->v) || v->layer_stride % 8 != 0 || v->token_stride % 8 != 0) return KVH_E_ALIGN;
+  return KVH_OK;
+}
+
+__global__ __launch_bounds__(kBlockThreads) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                              size_t n16) {
+  size_t i = (size_t)blockIdx.x * (kBlockThreads * 4) + threadIdx.x;
+  uint4 r[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + (size_t)u * kBlockThreads < n16) r[u] = src[i + (size_t)u * kBlockThreads];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + (size_t)u * kBlockThreads < n16) dst[i + (size_t)u * kBlockThreads] = r[u];
+}
+
+}  // namespace
+}  // namespace kvh
+
+using namespace kvh;
+
+extern "C" {
+
+int kvh_num_levels(void) { return 3; }
+
+int kvh_level_bits(int level) { return level_bits(level); }
+
+size_t kvh_blob_size(int l, int n_tokens, int c, int level) {
+  int bits = level_bits(level);
+  if (bits < 0 || check_shape(l, n_tokens, c) != KVH_OK) return 0;
+  return kHeaderBytes + (size_t)l * layer_geom(n_tokens, c, bits).layer_bytes();
+}
+
+int kvh_encode(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int level, void* blob_dev, size_t blob_cap,
+               void* stream) {
+  if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (int rc = check_view(kv)) return rc;
+  if (level_bits(level) < 0) return KVH_E_LEVEL;
+  if (int rc = check_shape(l, N, c)) return rc;
+  if (blob_cap < kvh_blob_size(l, N, c, level)) return KVH_E_SIZE;
+  if (!aligned16(blob_dev)) return KVH_E_ALIGN;
+  EncodeParams a{};
+  a.items = nullptr;
+  a.one = kvh_enc_item{blob_dev, 0, N, level};
+  a.k = static_cast<const uint16_t*>(kv->k);
+  a.v = static_cast<const uint16_t*>(kv->v);
+  a.layer_stride = kv->layer_stride;
+  a.token_stride = kv->token_stride;
+  a.l = l;
+  a.c = c;
+  return launch_encode(a, dt, 1, N, static_cast<hipStream_t>(stream));
+}
+
+int kvh_encode_chunked(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int chunk, const int8_t* levels,
+                       void* blobs_dev, const size_t* blob_offsets, size_t cap, void* stream) {
+  if (blobs_dev == nullptr || levels == nullptr || blob_offsets == nullptr || (dt != KVH_F16 && dt != KVH_BF16))
+    return KVH_E_ARG;
+  if (int rc = check_view(kv)) return rc;
+  if (int rc = check_shape(l, N, c)) return rc;
+  if (chunk < kGroup || chunk % kGroup != 0) return KVH_E_SHAPE;
+  if (!aligned16(blobs_dev)) return KVH_E_ALIGN;
+  const int n_chunks = (N + chunk - 1) / chunk;
+  // validate everything before the first launch
+  for (int i = 0; i < n_chunks; ++i) {
+    const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
+    if (level_bits(levels[i]) < 0) return KVH_E_LEVEL;
+    if (blob_offsets[i] % 16 != 0) return KVH_E_ALIGN;
+    const size_t need = kvh_blob_size(l, n, c, levels[i]);
+    if (blob_offsets[i] > cap || cap - blob_offsets[i] < need) return KVH_E_SIZE;
+  }
+  EncodeParams a{};
+  a.items = nullptr;
+  a.k = static_cast<const uint16_t*>(kv->k);
+  a.v = static_cast<const uint16_t*>(kv->v);
+  a.layer_stride = kv->layer_stride;
+  a.token_stride = kv->token_stride;
+  a.l = l;
+  a.c = c;
+  for (int i = 0; i < n_chunks; ++i) {
+    const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
+    a.one = kvh_enc_item{static_cast<uint8_t*>(blobs_dev) + blob_offsets[i], (int64_t)i * chunk, n, levels[i]};
+    if (int rc = launch_encode(a, dt, 1, n, static_cast<hipStream_t>(stream))) return rc;
+  }
+  return KVH_OK;
+}
+
+int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                     const kvh_kv_view* src, void* stream) {
+  if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (int rc = check_view(src)) return rc;
+  if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
+  EncodeParams a{};
+  a.items = items_dev;
+  a.k = static_cast<const uint16_t*>(src->k);
+  a.v = static_cast<const uint16_t*>(src->v);
+  a.layer_stride = src->layer_stride;
+  a.token_stride = src->token_stride;
+  a.l = l;
+  a.c = c;
+  return launch_encode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
+int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, int level, const kvh_kv_view* dst,
+               int64_t dst_token0, const int32_t* page_table_dev, int block_tokens, int32_t* status_dev, void* stream) {
+  if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16) || dst_token0 < 0) return KVH_E_ARG;
+  if (int rc = check_view(dst)) return rc;
+  if (level_bits(level) < 0) return KVH_E_LEVEL;
+  if (int rc = check_shape(l, n_tokens, c)) return rc;
+  if (page_table_dev != nullptr && block_tokens < 1) return KVH_E_ARG;
+  if (dst_token0 + n_tokens > INT32_MAX) return KVH_E_ARG;
+  if (!aligned16(blob_dev)) return KVH_E_ALIGN;
+  DecodeParams a{};
+  a.items = nullptr;
+  a.one = kvh_item{blob_dev, n_tokens, level, dst_token0, page_table_dev};
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
+  return launch_decode(a, dt, 1, n_tokens, static_cast<hipStream_t>(stream));
+}
+
+int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                     const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream) {
+  if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16) ||
+      block_tokens < 1)
+    return KVH_E_ARG;
+  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
+  DecodeParams a{};
+  a.items = items_dev;
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = block_tokens;
+  return launch_decode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
+int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
+  if (dst_dev == nullptr || src_dev == nullptr || bytes == 0) return KVH_E_ARG;
+  if (bytes % 16 != 0 || !aligned16(dst_dev) || !aligned16(src_dev)) return KVH_E_ALIGN;
+  const size_t n16 = bytes / 16;
+  const size_t per_block = (size_t)kBlockThreads * 4;
+  const size_t blocks = (n16 + per_block - 1) / per_block;
+  if (blocks > 0x7fffffffu) return KVH_E_SIZE;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(kBlockThreads), 0, static_cast<hipStream_t>(stream),
+                     static_cast<uint4*>(dst_dev), static_cast<const uint4*>(src_dev), n16);
+  KVH_HIP_CHECK_LAUNCH();
+  return KVH_OK;
+}
+
+const char* kvh_strerror(int status) {
+  switch (status) {
+    case KVH_OK: return "ok";
+    case KVH_E_ARG: return "bad argument (null pointer, dtype, offset, block size or item count)";
+    case KVH_E_LEVEL: return "level outside 0..2";
+    case KVH_E_SHAPE: return "bad shape (l, n >= 1; c and chunk multiples of 128)";
+    case KVH_E_SIZE: return "blob capacity too small";
+    case KVH_E_ALIGN: return "pointer or stride breaks the 16-byte alignment rule";
+    case KVH_E_HIP: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,116 @@
+// Shared pieces of the HIP implementation: blob geometry, the 16-bit float conversions and
+// the per-group parameters.  gfx950 only.  Nothing here is used by the CPU oracle.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kvh.h"
+
+namespace kvh {
+
+constexpr int kGroup = 128;        // tokens per K group and channels per V group
+constexpr int kHeaderBytes = 64;
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kLaneCh = 8;         // channels owned by one lane: 8 x 16 bit = one 128-bit access
+constexpr int kStripCh = kWave * kLaneCh;  // 512 channels = 1 KiB of 16-bit data per wave access
+constexpr int kBlockThreads = 256; // 4 waves
+constexpr int kWavesPerBlock = kBlockThreads / kWave;
+constexpr uint32_t kMagic = 0x3148564Bu;  // "KVH1" read as a little-endian u32
+
+__host__ __device__ inline int level_bits(int level) { return level == 0 ? 8 : level == 1 ? 4 : level == 2 ? 2 : -1; }
+__host__ __device__ inline size_t pad16(size_t x) { return (x + 15) & ~size_t(15); }
+
+// Byte sizes of the four sections of one layer.
+struct LayerGeom {
+  size_t kmeta, codes, vmeta;  // kcodes and vcodes have the same size
+  size_t row_bytes;            // one packed token row
+  __host__ __device__ size_t layer_bytes() const { return kmeta + vmeta + 2 * codes; }
+};
+
+__host__ __device__ inline LayerGeom layer_geom(int n, int c, int bits) {
+  LayerGeom g;
+  g.row_bytes = size_t(c) * bits / 8;
+  g.kmeta = pad16(size_t((n + kGroup - 1) / kGroup) * c * 4);
+  g.codes = pad16(size_t(n) * g.row_bytes);
+  g.vmeta = pad16(size_t(n) * (c / kGroup) * 4);
+  return g;
+}
+
+// ---- 16-bit float <-> fp32 ------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ float t16_to_f32(uint32_t bits16) {
+  if constexpr (DT == KVH_F16) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);  // v_cvt_f32_f16, exact
+  } else {
+    return __builtin_bit_cast(float, bits16 << 16);
+  }
+}
+
+// Round to nearest even.  Finite inputs only (a NaN would not stay a NaN in the bf16 branch).
+template <int DT>
+__device__ __forceinline__ uint32_t f32_to_t16(float f) {
+  if constexpr (DT == KVH_F16) {
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);  // v_cvt_f16_f32 under the default RNE mode
+  } else {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  }
+}
+
+// ---- group parameters -------------------------------------------------------------------------
+// meta = mn | mx << 16 (raw 16-bit patterns as stored in the blob).
+struct GroupParams {
+  float mn;      // f32(mn)
+  float scale;   // r / L, or 0 for a degenerate group
+  uint32_t top;  // what code L decodes to: mx, or mn for a degenerate group
+};
+
+template <int DT, int BITS>
+__device__ __forceinline__ GroupParams decode_params(uint32_t meta) {
+  constexpr float L = float((1 << BITS) - 1);
+  GroupParams p;
+  p.mn = t16_to_f32<DT>(meta & 0xffffu);
+  float r = t16_to_f32<DT>(meta >> 16) - p.mn;
+  bool degenerate = r < 0x1p-100f;
+  p.scale = degenerate ? 0.0f : r / L;  // IEEE division (correctly rounded)
+  p.top = degenerate ? (meta & 0xffffu) : (meta >> 16);
+  return p;
+}
+
+template <int BITS>
+__device__ __forceinline__ float encode_inv(float mn, float mx) {
+  constexpr float L = float((1 << BITS) - 1);
+  float r = mx - mn;
+  return r < 0x1p-100f ? 0.0f : L / r;
+}
+
+// ---- kernel parameter blocks and launchers (defined next to their kernels) -----------------------
+struct DecodeParams {
+  const kvh_item* items;  // device array of jobs, or nullptr: decode `one`
+  kvh_item one;
+  uint16_t* k;
+  uint16_t* v;
+  int64_t layer_stride, token_stride;  // elements
+  int32_t* status;                     // nullable; indexed by item
+  int l, c, block_tokens;
+};
+
+struct EncodeParams {
+  const kvh_enc_item* items;  // device array of jobs, or nullptr: encode `one`
+  kvh_enc_item one;
+  const uint16_t* k;
+  const uint16_t* v;
+  int64_t layer_stride, token_stride;  // elements
+  int l, c;
+};
+
+int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
+int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
+
+#define KVH_HIP_CHECK_LAUNCH()                          \
+  do {                                                  \
+    if (hipGetLastError() != hipSuccess) return KVH_E_HIP; \
+  } while (0)
+
+}  // namespace kvh

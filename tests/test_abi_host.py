@@ -1,0 +1,124 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol include/kvh.h declares,
+its size calculator agrees with the oracle's closed form, and argument errors are reported on
+the host before anything is launched (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvh.h")
+LIB = os.path.join(ROOT, "paper_2509_00105_amd", "libkvh.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2509_00105_amd import build
+
+        build.build()
+    import paper_2509_00105_amd.binding as b
+
+    return b.lib()
+
+
+def declared_symbols():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(kvh_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) >= {"kvh_encode", "kvh_decode", "kvh_encode_batch", "kvh_decode_batch", "kvh_encode_chunked",
+                          "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe"}
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_level_table_and_blob_size_agree_with_oracle(lib):
+    assert lib.kvh_num_levels() == oracle.num_levels() == 3
+    assert [lib.kvh_level_bits(i) for i in range(-2, 5)] == [oracle.level_bits(i) for i in range(-2, 5)]
+    rng = np.random.default_rng(0)
+    for _ in range(500):
+        l, n, m, lv = int(rng.integers(0, 90)), int(rng.integers(0, 3000)), int(rng.integers(0, 20)), int(rng.integers(-1, 4))
+        c = 128 * m + (64 if rng.random() < 0.1 else 0)
+        assert lib.kvh_blob_size(l, n, c, lv) == oracle.blob_size(l, n, c, lv), (l, n, c, lv)
+    assert lib.kvh_blob_size(32, 256, 1024, 2) == 4_718_656
+
+
+def test_strerror_covers_every_status(lib):
+    seen = {lib.kvh_strerror(s) for s in range(-6, 1)}
+    assert len(seen) == 7 and b"unknown status" not in seen
+    assert lib.kvh_strerror(-99) == b"unknown status"
+
+
+def test_argument_errors_are_found_on_the_host(lib):
+    """Every call below must be rejected before a launch (fake, suitably aligned pointers)."""
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("fake device pointers: run only where nothing could be launched")
+    from paper_2509_00105_amd.binding import _KVView
+
+    P = 0x10000
+    view = _KVView(P, P, 1024 * 256, 1024)
+    v = ctypes.byref(view)
+    E_ARG, E_LEVEL, E_SHAPE, E_SIZE, E_ALIGN = -1, -2, -3, -4, -5
+    big = 1 << 40
+    enc = lib.kvh_encode
+    assert enc(None, 0, 1, 128, 1024, 0, P, big, None) == E_ARG
+    assert enc(v, 0, 1, 128, 1024, 0, None, big, None) == E_ARG
+    assert enc(v, 2, 1, 128, 1024, 0, P, big, None) == E_ARG
+    assert enc(v, 0, 1, 128, 1024, 3, P, big, None) == E_LEVEL
+    assert enc(v, 0, 1, 128, 1024, -1, P, big, None) == E_LEVEL
+    assert enc(v, 0, 0, 128, 1024, 0, P, big, None) == E_SHAPE
+    assert enc(v, 0, 1, 0, 1024, 0, P, big, None) == E_SHAPE
+    assert enc(v, 0, 1, 128, 1000, 0, P, big, None) == E_SHAPE
+    assert enc(v, 0, 1, 128, 1024, 0, P, lib.kvh_blob_size(1, 128, 1024, 0) - 1, None) == E_SIZE
+    assert enc(v, 0, 1, 128, 1024, 0, P + 8, big, None) == E_ALIGN
+    assert enc(ctypes.byref(_KVView(P + 2, P, 1024, 1024)), 0, 1, 128, 1024, 0, P, big, None) == E_ALIGN
+    assert enc(ctypes.byref(_KVView(P, P, 1024, 1020)), 0, 1, 128, 1024, 0, P, big, None) == E_ALIGN
+    assert enc(ctypes.byref(_KVView(None, P, 1024, 1024)), 0, 1, 128, 1024, 0, P, big, None) == E_ARG
+
+    dec = lib.kvh_decode
+    assert dec(None, 0, 1, 128, 1024, 0, v, 0, None, 16, None, None) == E_ARG
+    assert dec(P, 0, 1, 128, 1024, 0, None, 0, None, 16, None, None) == E_ARG
+    assert dec(P, 0, 1, 128, 1024, 0, v, -1, None, 16, None, None) == E_ARG
+    assert dec(P, 0, 1, 128, 1024, 7, v, 0, None, 16, None, None) == E_LEVEL
+    assert dec(P, 0, 1, 128, 192, 0, v, 0, None, 16, None, None) == E_SHAPE
+    assert dec(P, 0, 1, 128, 1024, 0, v, 0, P, 0, None, None) == E_ARG
+    assert dec(P + 4, 0, 1, 128, 1024, 0, v, 0, None, 16, None, None) == E_ALIGN
+    assert dec(P, 0, 1, 128, 1024, 0, v, 2**31 - 64, None, 16, None, None) == E_ARG
+
+    lv = (ctypes.c_int8 * 2)(0, 1)
+    off = (ctypes.c_size_t * 2)(0, 1 << 20)
+    ch = lib.kvh_encode_chunked
+    assert ch(v, 0, 1, 256, 1024, 100, lv, P, off, big, None) == E_SHAPE        # chunk not a multiple of 128
+    assert ch(v, 0, 1, 256, 1024, 128, None, P, off, big, None) == E_ARG
+    assert ch(v, 0, 1, 256, 1024, 128, (ctypes.c_int8 * 2)(0, 5), P, off, big, None) == E_LEVEL
+    assert ch(v, 0, 1, 256, 1024, 128, lv, P, (ctypes.c_size_t * 2)(0, 8), big, None) == E_ALIGN
+    assert ch(v, 0, 1, 256, 1024, 128, lv, P, off, (1 << 20) + 100, None) == E_SIZE
+
+    assert lib.kvh_encode_batch(None, 1, 256, 0, 1, 1024, v, None) == E_ARG
+    assert lib.kvh_encode_batch(P, 0, 256, 0, 1, 1024, v, None) == E_ARG
+    assert lib.kvh_encode_batch(P, 70000, 256, 0, 1, 1024, v, None) == E_ARG
+    assert lib.kvh_encode_batch(P, 1, 256, 0, 1, 100, v, None) == E_SHAPE
+    assert lib.kvh_decode_batch(None, 1, 256, 0, 1, 1024, v, 16, None, None) == E_ARG
+    assert lib.kvh_decode_batch(P, 1, 256, 0, 1, 1024, v, 0, None, None) == E_ARG
+    assert lib.kvh_decode_batch(P, 1, 0, 0, 1, 1024, v, 16, None, None) == E_SHAPE
+    assert lib.kvh_copy_probe(P, P + 4096, 100, None) == E_ALIGN
+    assert lib.kvh_copy_probe(None, P, 4096, None) == E_ARG
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+
+    import paper_2509_00105_amd as kvh
+
+    k = torch.zeros((1, 128, 128), dtype=torch.float16)
+    with pytest.raises(ValueError):
+        kvh.encode(k, k, 0)
