@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV level codec hot path on one MI355X.
+
+One step = one pass of the whole hot path over the Llama-3-8B-shaped 8K-token KV
+(32 layers x 8192 tokens x 1024 channels, K and V, bf16, 256-token chunks): for each of the
+three levels, encode all 32 chunks in one batched launch and decode them back in one batched
+launch (6 kernels, 6 GiB of uncompressed KV through the codec per step).  Inputs, blobs and
+outputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: the whole-step throughput in GB/s of uncompressed KV, per-kernel
+figures, the HBM roofline of the dominant kernel (algorithmic bytes / HIP-event duration) and
+the CPU oracle timed on the host cores over a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_8k", choices=["llama3_8b_8k", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--cpu-sample-chunks", type=int, default=8)
+    return ap.parse_args()
+
+
+def algorithmic_bytes(l, n_tokens_total, c, bits, n_chunks, chunk):
+    """Bytes one encode or decode launch must move: the uncompressed KV once plus the blobs once."""
+    import paper_2509_00105_amd as kvh
+
+    level = {8: 0, 4: 1, 2: 2}[bits]
+    unc = 2 * l * n_tokens_total * c * 2
+    blobs = n_chunks * kvh.blob_size(l, chunk, c, level)
+    return unc, blobs
+
+
+def cpu_baseline(kv_host_chunks, dt, l, chunk, c, gpu_blobs):
+    """Time the oracle (as it stands) on the host cores over the sampled chunks; also check the
+    GPU's blobs for those chunks against it."""
+    import concurrent.futures as cf
+
+    import numpy as np
+
+    import oracle
+
+    cores = min(os.cpu_count() or 1, 16, max(1, len(kv_host_chunks) * 3))
+    oracle.lib()
+
+    def job(args):
+        ci, level = args
+        k, v = kv_host_chunks[ci]
+        blob = oracle.encode(k, v, dt, level)
+        oracle.decode(blob, dt, l, chunk, c, level)
+        return ci, level, blob
+
+    tasks = [(ci, level) for level in range(3) for ci in range(len(kv_host_chunks))]
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(max_workers=cores) as ex:
+        results = list(ex.map(job, tasks))
+    wall = time.perf_counter() - t0
+    unc_bytes = 2 * l * chunk * c * 2
+    total = unc_bytes * 2 * len(tasks)  # encode + decode of every (chunk, level)
+    parity = all(np.array_equal(blob, gpu_blobs[(ci, level)]) for ci, level, blob in results)
+    return {"value": total / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of the workload's 256-token chunks (%d MiB uncompressed), encode+decode at 8/4/2 bits, "
+                      "one (chunk, level) per thread" % (len(kv_host_chunks), len(kv_host_chunks) * unc_bytes >> 20),
+            "wall_s": wall}, parity
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus %d is not supported. "
+              "The value reported at --gpus 1 is that GPU's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import kv_inputs as gen
+    import paper_2509_00105_amd as kvh
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (the HIP path has no CPU fallback)"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = gen.CONFIGS[args.workload]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    n_chunks = N // chunk
+    tdt = torch.float16 if dt == gen.F16 else torch.bfloat16
+
+    kv = gen.make_kv_device(l, N, c, dt, cfg.seed, device=dev, drift=cfg.drift)   # [2][l][N][c]
+    out = torch.empty_like(kv)
+    blobs, enc_items, dec_items, status = {}, {}, {}, {}
+    for level in range(3):
+        size = kvh.blob_size(l, chunk, c, level)
+        blobs[level] = torch.empty(n_chunks * size, dtype=torch.uint8, device=dev)
+        ptrs = [blobs[level].data_ptr() + i * size for i in range(n_chunks)]
+        enc_items[level] = kvh.make_enc_items(ptrs, [i * chunk for i in range(n_chunks)], [chunk] * n_chunks,
+                                              [level] * n_chunks, dev)
+        dec_items[level] = kvh.make_dec_items(ptrs, [chunk] * n_chunks, [level] * n_chunks,
+                                              [i * chunk for i in range(n_chunks)], [0] * n_chunks, dev)
+        status[level] = torch.zeros(n_chunks, dtype=torch.int32, device=dev)
+
+    stream = torch.cuda.Stream()
+    kernels = [("encode", lv) for lv in range(3)] + [("decode", lv) for lv in range(3)]
+
+    def launch(kind, level):
+        if kind == "encode":
+            kvh.encode_batch(enc_items[level], n_chunks, chunk, kv[0], kv[1], stream=stream)
+        else:
+            kvh.decode_batch(dec_items[level], n_chunks, chunk, out[0], out[1], status=status[level], stream=stream)
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            for kind, level in kernels:
+                launch(kind, level)
+        torch.cuda.synchronize()
+        # timed region: exactly `steps` steps; every kernel is bracketed by events on its own stream
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(kernels) + 1)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            ev[s][0].record(stream)
+            for j, (kind, level) in enumerate(kernels):
+                launch(kind, level)
+                ev[s][j + 1].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+
+    assert all(int(status[lv].abs().sum().item()) == 0 for lv in range(3)), "a decode reported a header mismatch"
+    step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
+    total_ms = ev[0][0].elapsed_time(ev[-1][-1])
+    ms_per_step = total_ms / args.steps
+    unc = 2 * l * N * c * 2
+
+    per_kernel = []
+    for j, (kind, level) in enumerate(kernels):
+        bits = kvh.level_bits(level)
+        durs = [ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(args.steps)]
+        avg = sum(durs) / len(durs)
+        u, b = algorithmic_bytes(l, N, c, bits, n_chunks, chunk)
+        per_kernel.append({"kernel": "%s_kernel" % kind, "op": kind, "bits": bits, "avg_ms": avg, "min_ms": min(durs),
+                           "uncompressed_GBps": u / avg / 1e6, "algorithmic_bytes": u + b,
+                           "hbm_GBps": (u + b) / avg / 1e6, "hbm_frac": (u + b) / avg / 1e6 / HBM_PEAK_GBPS})
+    dominant = max(per_kernel, key=lambda r: r["avg_ms"])
+    dec2 = [r for r in per_kernel if r["op"] == "decode"]
+
+    result = {
+        "metric": "KV decode & encode GB/s (uncompressed bytes) per level; % of HBM peak",
+        "value": 6 * unc / ms_per_step / 1e6,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",  # statistics, quantisation and dequantisation are computed in fp32; I/O is bf16/fp16
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": l, "tokens": N, "channels": c, "io_dtype": gen.DTYPE_NAMES[dt],
+                   "chunk_tokens": chunk, "levels_bits": [8, 4, 2],
+                   "step": "encode_batch + decode_batch of all %d chunks at each of the 3 levels (6 launches)" % n_chunks},
+        "roofline": {"bound": "hbm", "kernel": "%s %d-bit" % (dominant["op"], dominant["bits"]),
+                     "achieved": dominant["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": dominant["hbm_frac"], "traffic": None},
+        "decode_hbm_frac": {str(r["bits"]): r["hbm_frac"] for r in dec2},
+        "kernels": per_kernel,
+        "host_wall_ms_per_step": wall * 1e3 / args.steps,
+        "step_ms_min": min(step_ms),
+    }
+
+    if not args.no_cpu_baseline:
+        m = max(1, min(args.cpu_sample_chunks, n_chunks))
+        picks = sorted(set(int(round(i * (n_chunks - 1) / max(1, m - 1))) for i in range(m)))
+        host_chunks, gpu_blobs = [], {}
+        for ci in picks:
+            sl = kv[:, :, ci * chunk:(ci + 1) * chunk].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            host_chunks.append((sl[0], sl[1]))
+        for level in range(3):
+            size = kvh.blob_size(l, chunk, c, level)
+            for j, ci in enumerate(picks):
+                gpu_blobs[(j, level)] = blobs[level][ci * size:(ci + 1) * size].cpu().numpy()
+        base, parity = cpu_baseline(host_chunks, dt, l, chunk, c, gpu_blobs)
+        result["cpu_baseline"] = base
+        result["sampled_blobs_match_oracle"] = bool(parity)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,46 +1,115 @@
 // Level decoder: unpack b-bit codes, dequantise with the stored (min, max) of each group and
 // write fp16/bf16 KV rows, contiguous or through a page table (the "decompression" whose
-// overhead the paper's estimator profiles; Design section).  Pure streaming kernel: every
-// lane owns 8 channels, so every store is one 128-bit access and a wave writes 1 KiB of a
-// token row per instruction; K metadata (per channel) lives in registers across the rows of
-// a tile, V metadata (per token and head) is fetched by one lane per group and broadcast.
+// overhead the paper's estimator profiles; Design section).
+//
+// Pure streaming kernel, no LDS and no block-level cooperation: the unit of work is one wave
+// decoding 16 consecutive token rows of one 512-channel strip.  A lane owns 8 channels, so each
+// store is one 128-bit access and the wave writes 1 KiB of a row per instruction.  K metadata
+// (per channel) is turned into fp32 parameters once per unit and stays in registers; V
+// metadata (per token and head) is prepared by one lane per group and broadcast.  The rare
+// groups whose top code does not land exactly on the stored maximum select a slower row loop
+// through a wave-uniform branch.
 #include "kvh_common.hpp"
 
 namespace kvh {
 
-constexpr int kDecRows = 16;                            // rows per wave
-constexpr int kDecTile = kDecRows * kWavesPerBlock;     // 64 tokens per block (divides the K group)
+#ifndef KVH_DEC_NT
+#define KVH_DEC_NT 1  // non-temporal stores: decoded KV is not re-read by this kernel
+#endif
+
+constexpr int kDecRows = 16;  // token rows per wave (= lanes / 4 heads per strip)
+static_assert(kGroup % kDecRows == 0, "a unit must not straddle K token-groups");
+static_assert(kDecRows * (kStripCh / kGroup) == kWave, "one lane per (row, head) group of a unit");
+
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+// Load through a pointer known to be in global memory (scalar or clang vector types only).
+template <typename T>
+__device__ __forceinline__ T gload(const uint8_t* p) {
+  return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+
+__device__ __forceinline__ void gstore16(uint16_t* p, const uint4& v) {
+  auto* g = reinterpret_cast<__attribute__((address_space(1))) uintx4*>(reinterpret_cast<uintptr_t>(p));
+  uintx4 x = {v.x, v.y, v.z, v.w};
+#if KVH_DEC_NT
+  __builtin_nontemporal_store(x, g);
+#else
+  *g = x;
+#endif
+}
+
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values -> two 16-bit values in one word (element 0 in the low half), each rounded to
+// nearest even.  gfx950 has packed converts for both types.
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  floatx2 f = {a, b};
+  if constexpr (DT == KVH_F16) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
+  } else {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+  }
+}
 
 template <int BITS>
 struct Codes;
 template <>
 struct Codes<8> {
-  uint2 w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint2*>(p); }
+  uintx2 w;
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx2>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return ((j < 4 ? w.x : w.y) >> (8 * (j & 3))) & 0xffu; }
 };
 template <>
 struct Codes<4> {
   uint32_t w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint32_t*>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint32_t>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return (w >> (4 * j)) & 0xfu; }
 };
 template <>
 struct Codes<2> {
   uint32_t w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = *reinterpret_cast<const uint16_t*>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint16_t>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return (w >> (2 * j)) & 0x3u; }
 };
 
-template <int DT, int BITS>
-__device__ __forceinline__ uint32_t dequant1(uint32_t q, const GroupParams& p) {
-  constexpr uint32_t L = (1u << BITS) - 1u;
-  float y = __builtin_fmaf((float)q, p.scale, p.mn);
+// fp32 reconstruction of one code; the 16-bit rounding happens in pack2.
+__device__ __forceinline__ float recon(uint32_t q, float scale, float mn) {
+  float y = __builtin_fmaf((float)q, scale, mn);
   // The definition rounds twice (fma to fp32, then fp32 to the 16-bit type).  Keep the compiler
   // from merging the two into a mixed-precision fma that rounds once straight to fp16.
   asm("" : "+v"(y));
-  uint32_t h = f32_to_t16<DT>(y);
-  return q == L ? p.top : h;
+  return y;
+}
+
+// Does code L need the explicit "decode to the stored maximum" rule for this group?
+template <int DT, int BITS>
+__device__ __forceinline__ bool top_needs_fix(const GroupParams& p) {
+  constexpr uint32_t L = (1u << BITS) - 1u;
+  return (pack2<DT>(recon(L, p.scale, p.mn), 0.0f) & 0xffffu) != p.top;
+}
+
+// Dequantise the 8 codes of one lane for one row.  param(j) gives the parameters of channel j.
+template <int DT, int BITS, bool FIX, typename P>
+__device__ __forceinline__ uint4 dequant8(const Codes<BITS>& cw, P&& param) {
+  constexpr uint32_t L = (1u << BITS) - 1u;
+  uint32_t w[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const GroupParams& p0 = param(2 * j);
+    const GroupParams& p1 = param(2 * j + 1);
+    uint32_t q0 = cw.get(2 * j), q1 = cw.get(2 * j + 1);
+    w[j] = pack2<DT>(recon(q0, p0.scale, p0.mn), recon(q1, p1.scale, p1.mn));
+    if constexpr (FIX) {
+      if (q0 == L) w[j] = (w[j] & 0xffff0000u) | p0.top;
+      if (q1 == L) w[j] = (w[j] & 0x0000ffffu) | (p1.top << 16);
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // Physical row of logical position s.
@@ -48,24 +117,42 @@ __device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_t
   if (page_table == nullptr) return (int32_t)s;
   uint32_t su = (uint32_t)s, bt = (uint32_t)block_tokens;
   uint32_t blk = su / bt;
-  return page_table[blk] * block_tokens + (int32_t)(su - blk * bt);
+  return gload<int32_t>(reinterpret_cast<const uint8_t*>(page_table + blk)) * block_tokens + (int32_t)(su - blk * bt);
+}
+
+template <int DT, int BITS, bool FIX, typename P>
+__device__ __forceinline__ void decode_rows(const uint8_t* codes, size_t row_bytes, uint32_t lane_code_off,
+                                            uint16_t* dst, int64_t token_stride, uint32_t lane_dst_off,
+                                            const int32_t (&rows)[kDecRows], int t0, int n, P&& param_of_row) {
+  Codes<BITS> cw[kDecRows];
+#pragma unroll
+  for (int i = 0; i < kDecRows; ++i) {
+    int t = t0 + i;
+    t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
+    cw[i].load(codes + (size_t)t * row_bytes + lane_code_off);
+  }
+#pragma unroll
+  for (int i = 0; i < kDecRows; ++i) {
+    if (t0 + i < n) {  // wave-uniform
+      uint4 out = dequant8<DT, BITS, FIX>(cw[i], param_of_row(i));
+      gstore16(dst + (int64_t)rows[i] * token_stride + lane_dst_off, out);
+    }
+  }
 }
 
 template <int DT, int BITS>
-__device__ __forceinline__ void decode_tile(const DecodeParams& a, const kvh_item& it, const uint8_t* layer_base,
-                                            const LayerGeom& geo, int lam, bool is_v, int t_begin, int strip) {
+__device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, const uint8_t* layer_base,
+                                            const LayerGeom& geo, int lam, bool is_v, int t0, int strip) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x >> 6;
   const int n = it.n_tokens;
   const int c = a.c;
   const int ch0 = strip * kStripCh + lane * kLaneCh;
   const bool active = ch0 < c;
-  const int t_first = t_begin + wave;  // this wave's rows: t_first + 4 * i
 
-  // Row i's destination is computed by lane i, then handed to the whole wave.
+  // Row i's destination is computed by lane i, then handed to the whole wave as a scalar.
   int32_t my_row = 0;
   {
-    int t = t_first + kWavesPerBlock * (lane & (kDecRows - 1));
+    int t = t0 + (lane & (kDecRows - 1));
     if (t < n) my_row = physical_row(it.dst_token0 + t, it.page_table, a.block_tokens);
   }
   int32_t rows[kDecRows];
@@ -76,125 +163,121 @@ __device__ __forceinline__ void decode_tile(const DecodeParams& a, const kvh_ite
   const uint8_t* kcodes = kmeta + geo.kmeta;
   const uint8_t* vmeta = kcodes + geo.codes;
   const uint8_t* vcodes = vmeta + geo.vmeta;
-  uint16_t* dst = (is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride + ch0;
-  const uint8_t* codes = (is_v ? vcodes : kcodes) + (size_t)ch0 * BITS / 8;
+  uint16_t* dst = (is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride;
+  const uint32_t lane_dst_off = (uint32_t)ch0;
+  const uint32_t lane_code_off = (uint32_t)ch0 * BITS / 8;
 
   if (!is_v) {
-    if (!active) return;
-    const int g = t_begin / kGroup;
-    const uint4* mp = reinterpret_cast<const uint4*>(kmeta + ((size_t)g * c + ch0) * 4);
-    uint4 m0 = mp[0], m1 = mp[1];
-    const uint32_t meta[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
     GroupParams gp[kLaneCh];
+    bool fix = false;
+    if (active) {
+      const int g = t0 / kGroup;
+      const uint8_t* mp = kmeta + ((size_t)g * c + ch0) * 4;
+      uintx4 m0 = gload<uintx4>(mp), m1 = gload<uintx4>(mp + 16);
+      const uint32_t meta[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
 #pragma unroll
-    for (int j = 0; j < kLaneCh; ++j) gp[j] = decode_params<DT, BITS>(meta[j]);
-
-    Codes<BITS> cw[kDecRows];
-#pragma unroll
-    for (int i = 0; i < kDecRows; ++i) {
-      int t = t_first + kWavesPerBlock * i;
-      t = t < n ? t : n - 1;
-      cw[i].load(codes + (size_t)t * geo.row_bytes);
-    }
-#pragma unroll
-    for (int i = 0; i < kDecRows; ++i) {
-      int t = t_first + kWavesPerBlock * i;
-      if (t < n) {
-        uint32_t h[kLaneCh];
-#pragma unroll
-        for (int j = 0; j < kLaneCh; ++j) h[j] = dequant1<DT, BITS>(cw[i].get(j), gp[j]);
-        uint4 out = {h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
-        *reinterpret_cast<uint4*>(dst + (int64_t)rows[i] * a.token_stride) = out;
+      for (int j = 0; j < kLaneCh; ++j) {
+        gp[j] = decode_params<DT, BITS>(meta[j]);
+        fix |= top_needs_fix<DT, BITS>(gp[j]);
       }
     }
+    const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+    if (!active) return;
+    auto param_of_row = [&](int) { return [&](int j) -> const GroupParams& { return gp[j]; }; };
+    if (any_fix)
+      decode_rows<DT, BITS, true>(kcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0, n,
+                                  param_of_row);
+    else
+      decode_rows<DT, BITS, false>(kcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0,
+                                   n, param_of_row);
   } else {
-    // One lane per (row, head) group of this wave's 16 rows x 4 heads fetches and prepares the
-    // parameters; every row then pulls its group's values from that lane.
+    // Lane (i, h) = (lane / 4, lane % 4) prepares the parameters of row i, head h of the strip;
+    // every row then pulls its group's three values from that lane.
     const int heads = c / kGroup;
     GroupParams mine = {0.0f, 0.0f, 0u};
+    bool fix = false;
     {
-      int t = t_first + kWavesPerBlock * (lane >> 2);
+      int t = t0 + (lane >> 2);
       int head = strip * (kStripCh / kGroup) + (lane & 3);
       if (t < n && head < heads) {
-        uint32_t meta = *reinterpret_cast<const uint32_t*>(vmeta + ((size_t)t * heads + head) * 4);
-        mine = decode_params<DT, BITS>(meta);
+        mine = decode_params<DT, BITS>(gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4));
+        fix = top_needs_fix<DT, BITS>(mine);
       }
     }
-    Codes<BITS> cw[kDecRows];
-    if (active) {
-#pragma unroll
-      for (int i = 0; i < kDecRows; ++i) {
-        int t = t_first + kWavesPerBlock * i;
-        t = t < n ? t : n - 1;
-        cw[i].load(codes + (size_t)t * geo.row_bytes);
-      }
-    }
+    const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+    GroupParams rp[kDecRows];
 #pragma unroll
     for (int i = 0; i < kDecRows; ++i) {
-      int t = t_first + kWavesPerBlock * i;
       int src = i * 4 + (lane >> 4);
-      GroupParams p;
-      p.mn = __shfl(mine.mn, src);
-      p.scale = __shfl(mine.scale, src);
-      p.top = __shfl(mine.top, src);
-      if (active && t < n) {
-        uint32_t h[kLaneCh];
-#pragma unroll
-        for (int j = 0; j < kLaneCh; ++j) h[j] = dequant1<DT, BITS>(cw[i].get(j), p);
-        uint4 out = {h[0] | h[1] << 16, h[2] | h[3] << 16, h[4] | h[5] << 16, h[6] | h[7] << 16};
-        *reinterpret_cast<uint4*>(dst + (int64_t)rows[i] * a.token_stride) = out;
-      }
+      rp[i].mn = __shfl(mine.mn, src);
+      rp[i].scale = __shfl(mine.scale, src);
+      rp[i].top = __shfl(mine.top, src);
     }
+    if (!active) return;
+    auto param_of_row = [&](int i) { return [&rp, i](int) -> const GroupParams& { return rp[i]; }; };
+    if (any_fix)
+      decode_rows<DT, BITS, true>(vcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0, n,
+                                  param_of_row);
+    else
+      decode_rows<DT, BITS, false>(vcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0,
+                                   n, param_of_row);
   }
 }
 
 __device__ __forceinline__ bool header_matches(const uint8_t* blob, int dt, int bits, int l, int n, int c,
                                                size_t total) {
-  const uint4* h = reinterpret_cast<const uint4*>(blob);
-  uint4 a = h[0], b = h[1];
+  uintx4 a = gload<uintx4>(blob), b = gload<uintx4>(blob + 16);
   return a.x == kMagic && a.y == (1u | (uint32_t)dt << 16 | (uint32_t)bits << 24) && a.z == (uint32_t)l &&
          a.w == (uint32_t)n && b.x == (uint32_t)c && b.y == ((uint32_t)kGroup | (uint32_t)kGroup << 16) &&
          b.z == (uint32_t)total && b.w == (uint32_t)((uint64_t)total >> 32);
 }
 
-// grid = (token tiles x strips, 2 * l, items)
+// grid = (ceil(units / 4), 2 * l, items); unit = (16-row tile, strip), strip fastest, one per wave.
 template <int DT>
 __global__ __launch_bounds__(kBlockThreads) void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
   kvh_item it;
   if (a.items != nullptr) {
-    it = a.items[item_idx];
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
+    uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16);
+    it.blob = reinterpret_cast<const void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
+    it.n_tokens = (int32_t)lo.z;
+    it.level = (int32_t)lo.w;
+    it.dst_token0 = (int64_t)((uint64_t)hi.x | (uint64_t)hi.y << 32);
+    it.page_table = reinterpret_cast<const int32_t*>((uint64_t)hi.z | (uint64_t)hi.w << 32);
   } else {
     it = a.one;
   }
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
-  const int tile = blockIdx.x / nstrips;
-  const int strip = blockIdx.x - tile * nstrips;
-  const int t_begin = tile * kDecTile;
-  if (it.n_tokens < 1 || t_begin >= it.n_tokens) return;
+  const int unit = blockIdx.x * kWavesPerBlock + wave;
+  const int tile = unit / nstrips;
+  const int strip = unit - tile * nstrips;
+  const int t0 = tile * kDecRows;
+  if (it.n_tokens < 1 || t0 >= it.n_tokens) return;
   const int bits = level_bits(it.level);
   const uint8_t* blob = static_cast<const uint8_t*>(it.blob);
   bool ok = bits > 0;
   LayerGeom geo = layer_geom(it.n_tokens, a.c, ok ? bits : 8);
   if (ok) ok = header_matches(blob, DT, bits, a.l, it.n_tokens, a.c, kHeaderBytes + (size_t)a.l * geo.layer_bytes());
   if (!ok) {
-    if (a.status != nullptr && threadIdx.x == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
+    if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
     return;
   }
   const int lam = blockIdx.y >> 1;
   const bool is_v = blockIdx.y & 1;
   const uint8_t* layer_base = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
   switch (bits) {
-    case 8: decode_tile<DT, 8>(a, it, layer_base, geo, lam, is_v, t_begin, strip); break;
-    case 4: decode_tile<DT, 4>(a, it, layer_base, geo, lam, is_v, t_begin, strip); break;
-    default: decode_tile<DT, 2>(a, it, layer_base, geo, lam, is_v, t_begin, strip); break;
+    case 8: decode_unit<DT, 8>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
+    case 4: decode_unit<DT, 4>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
+    default: decode_unit<DT, 2>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
   }
 }
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
-  const int tiles = (max_tokens + kDecTile - 1) / kDecTile;
-  dim3 grid((unsigned)(tiles * nstrips), (unsigned)(2 * a.l), (unsigned)n_items);
+  const int64_t units = (int64_t)((max_tokens + kDecRows - 1) / kDecRows) * nstrips;
+  dim3 grid((unsigned)((units + kWavesPerBlock - 1) / kWavesPerBlock), (unsigned)(2 * a.l), (unsigned)n_items);
   if (dt == KVH_F16)
     hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kBlockThreads), 0, stream, a);
   else
