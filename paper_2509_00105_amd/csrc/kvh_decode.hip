@@ -16,10 +16,21 @@ namespace kvh {
 #ifndef KVH_DEC_NT
 #define KVH_DEC_NT 1  // non-temporal stores: decoded KV is not re-read by this kernel
 #endif
+#ifndef KVH_DEC_NTL
+#define KVH_DEC_NTL 0  // non-temporal loads of the packed codes
+#endif
+#ifndef KVH_DEC_WAVES
+#define KVH_DEC_WAVES 4  // waves per block (waves are independent; this only shapes dispatch)
+#endif
+constexpr int kDecWaves = KVH_DEC_WAVES;
+constexpr int kDecThreads = kDecWaves * kWave;
 
-constexpr int kDecRows = 16;  // token rows per wave (= lanes / 4 heads per strip)
+#ifndef KVH_DEC_ROWS
+#define KVH_DEC_ROWS 16
+#endif
+constexpr int kDecRows = KVH_DEC_ROWS;  // token rows per wave
 static_assert(kGroup % kDecRows == 0, "a unit must not straddle K token-groups");
-static_assert(kDecRows * (kStripCh / kGroup) == kWave, "one lane per (row, head) group of a unit");
+static_assert(kDecRows * (kStripCh / kGroup) <= kWave, "one lane per (row, head) group of a unit");
 
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -28,6 +39,17 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 template <typename T>
 __device__ __forceinline__ T gload(const uint8_t* p) {
   return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+
+// Same, for the streamed code words.
+template <typename T>
+__device__ __forceinline__ T gload_stream(const uint8_t* p) {
+#if KVH_DEC_NTL
+  return __builtin_nontemporal_load(
+      reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  return gload<T>(p);
+#endif
 }
 
 __device__ __forceinline__ void gstore16(uint16_t* p, const uint4& v) {
@@ -61,19 +83,19 @@ struct Codes;
 template <>
 struct Codes<8> {
   uintx2 w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx2>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_stream<uintx2>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return ((j < 4 ? w.x : w.y) >> (8 * (j & 3))) & 0xffu; }
 };
 template <>
 struct Codes<4> {
   uint32_t w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint32_t>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_stream<uint32_t>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return (w >> (4 * j)) & 0xfu; }
 };
 template <>
 struct Codes<2> {
   uint32_t w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint16_t>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_stream<uint16_t>(p); }
   __device__ __forceinline__ uint32_t get(int j) const { return (w >> (2 * j)) & 0x3u; }
 };
 
@@ -120,34 +142,50 @@ __device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_t
   return gload<int32_t>(reinterpret_cast<const uint8_t*>(page_table + blk)) * block_tokens + (int32_t)(su - blk * bt);
 }
 
+// Compute and store the rows of one unit from codes already in registers.
 template <int DT, int BITS, bool FIX, typename P>
-__device__ __forceinline__ void decode_rows(const uint8_t* codes, size_t row_bytes, uint32_t lane_code_off,
-                                            uint16_t* dst, int64_t token_stride, uint32_t lane_dst_off,
-                                            const int32_t (&rows)[kDecRows], int t0, int n, P&& param_of_row) {
-  Codes<BITS> cw[kDecRows];
-#pragma unroll
-  for (int i = 0; i < kDecRows; ++i) {
-    int t = t0 + i;
-    t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
-    cw[i].load(codes + (size_t)t * row_bytes + lane_code_off);
-  }
+__device__ __forceinline__ void decode_rows(const Codes<BITS> (&cw)[kDecRows], uint16_t* dst, int64_t token_stride,
+                                            uint32_t lane_dst_off, const int32_t (&rows)[kDecRows], int t0, int n,
+                                            bool active, P&& param_of_row) {
 #pragma unroll
   for (int i = 0; i < kDecRows; ++i) {
     if (t0 + i < n) {  // wave-uniform
       uint4 out = dequant8<DT, BITS, FIX>(cw[i], param_of_row(i));
-      gstore16(dst + (int64_t)rows[i] * token_stride + lane_dst_off, out);
+      if (active) gstore16(dst + (int64_t)rows[i] * token_stride + lane_dst_off, out);
     }
   }
 }
 
+struct HeaderWords {
+  uintx4 a, b;
+};
+__device__ __forceinline__ HeaderWords load_header(const uint8_t* blob) {
+  return {gload<uintx4>(blob), gload<uintx4>(blob + 16)};
+}
+__device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int bits, int l, int n, int c,
+                                               size_t total) {
+  return h.a.x == kMagic && h.a.y == (1u | (uint32_t)dt << 16 | (uint32_t)bits << 24) && h.a.z == (uint32_t)l &&
+         h.a.w == (uint32_t)n && h.b.x == (uint32_t)c && h.b.y == ((uint32_t)kGroup | (uint32_t)kGroup << 16) &&
+         h.b.z == (uint32_t)total && h.b.w == (uint32_t)((uint64_t)total >> 32);
+}
+
+// One unit: every load the unit needs (header, page-table entries, metadata, codes) is issued
+// up front so that their latencies overlap; the header verdict is taken before anything is
+// stored.  The caller guarantees kvh_blob_size(l, n_tokens, c, level) readable bytes at the
+// blob pointer, so these loads stay inside the buffer whatever the header says.
 template <int DT, int BITS>
-__device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, const uint8_t* layer_base,
-                                            const LayerGeom& geo, int lam, bool is_v, int t0, int strip) {
+__device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
+                                            int t0, int strip) {
   const int lane = threadIdx.x & (kWave - 1);
   const int n = it.n_tokens;
   const int c = a.c;
-  const int ch0 = strip * kStripCh + lane * kLaneCh;
-  const bool active = ch0 < c;
+  const uint8_t* blob = static_cast<const uint8_t*>(it.blob);
+  const LayerGeom geo = layer_geom(n, c, BITS);
+  const HeaderWords hdr = load_header(blob);
+
+  const int ch_raw = strip * kStripCh + lane * kLaneCh;
+  const bool active = ch_raw < c;
+  const int ch0 = active ? ch_raw : 0;  // idle lanes of a partial strip shadow lane 0 and never store
 
   // Row i's destination is computed by lane i, then handed to the whole wave as a scalar.
   int32_t my_row = 0;
@@ -155,86 +193,88 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     int t = t0 + (lane & (kDecRows - 1));
     if (t < n) my_row = physical_row(it.dst_token0 + t, it.page_table, a.block_tokens);
   }
-  int32_t rows[kDecRows];
-#pragma unroll
-  for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
 
-  const uint8_t* kmeta = layer_base;
+  const uint8_t* kmeta = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
   const uint8_t* kcodes = kmeta + geo.kmeta;
   const uint8_t* vmeta = kcodes + geo.codes;
   const uint8_t* vcodes = vmeta + geo.vmeta;
   uint16_t* dst = (is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride;
   const uint32_t lane_dst_off = (uint32_t)ch0;
-  const uint32_t lane_code_off = (uint32_t)ch0 * BITS / 8;
+  const uint8_t* codes = (is_v ? vcodes : kcodes) + (uint32_t)ch0 * BITS / 8;
+  const int heads = c / kGroup;
+
+  // metadata: K = 8 channels of this lane; V = group (row lane/4, head lane%4) of this unit
+  uintx4 m0 = {0, 0, 0, 0}, m1 = {0, 0, 0, 0};
+  uint32_t vm = 0;
+  bool v_owner = false;
+  if (!is_v) {
+    const uint8_t* mp = kmeta + ((size_t)(t0 / kGroup) * c + ch0) * 4;
+    m0 = gload<uintx4>(mp);
+    m1 = gload<uintx4>(mp + 16);
+  } else {
+    int t = t0 + (lane >> 2);
+    int head = strip * (kStripCh / kGroup) + (lane & 3);
+    v_owner = (lane >> 2) < kDecRows && t < n && head < heads;
+    if (v_owner) vm = gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4);
+  }
+  Codes<BITS> cw[kDecRows];
+#pragma unroll
+  for (int i = 0; i < kDecRows; ++i) {
+    int t = t0 + i;
+    t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
+    cw[i].load(codes + (size_t)t * geo.row_bytes);
+  }
+
+  if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes())) {
+    if (a.status != nullptr && lane == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
+    return;
+  }
+  int32_t rows[kDecRows];
+#pragma unroll
+  for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
 
   if (!is_v) {
+    const uint32_t meta[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
     GroupParams gp[kLaneCh];
     bool fix = false;
-    if (active) {
-      const int g = t0 / kGroup;
-      const uint8_t* mp = kmeta + ((size_t)g * c + ch0) * 4;
-      uintx4 m0 = gload<uintx4>(mp), m1 = gload<uintx4>(mp + 16);
-      const uint32_t meta[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
 #pragma unroll
-      for (int j = 0; j < kLaneCh; ++j) {
-        gp[j] = decode_params<DT, BITS>(meta[j]);
-        fix |= top_needs_fix<DT, BITS>(gp[j]);
-      }
+    for (int j = 0; j < kLaneCh; ++j) {
+      gp[j] = decode_params<DT, BITS>(meta[j]);
+      fix |= top_needs_fix<DT, BITS>(gp[j]);
     }
     const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-    if (!active) return;
     auto param_of_row = [&](int) { return [&](int j) -> const GroupParams& { return gp[j]; }; };
     if (any_fix)
-      decode_rows<DT, BITS, true>(kcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0, n,
-                                  param_of_row);
+      decode_rows<DT, BITS, true>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
     else
-      decode_rows<DT, BITS, false>(kcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0,
-                                   n, param_of_row);
+      decode_rows<DT, BITS, false>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
   } else {
-    // Lane (i, h) = (lane / 4, lane % 4) prepares the parameters of row i, head h of the strip;
-    // every row then pulls its group's three values from that lane.
-    const int heads = c / kGroup;
     GroupParams mine = {0.0f, 0.0f, 0u};
     bool fix = false;
-    {
-      int t = t0 + (lane >> 2);
-      int head = strip * (kStripCh / kGroup) + (lane & 3);
-      if (t < n && head < heads) {
-        mine = decode_params<DT, BITS>(gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4));
-        fix = top_needs_fix<DT, BITS>(mine);
-      }
+    if (v_owner) {
+      mine = decode_params<DT, BITS>(vm);
+      fix = top_needs_fix<DT, BITS>(mine);
     }
     const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-    GroupParams rp[kDecRows];
-#pragma unroll
-    for (int i = 0; i < kDecRows; ++i) {
+    // every row pulls its group's three values from the lane that prepared them
+    auto param_of_row = [&](int i) {
       int src = i * 4 + (lane >> 4);
-      rp[i].mn = __shfl(mine.mn, src);
-      rp[i].scale = __shfl(mine.scale, src);
-      rp[i].top = __shfl(mine.top, src);
-    }
-    if (!active) return;
-    auto param_of_row = [&](int i) { return [&rp, i](int) -> const GroupParams& { return rp[i]; }; };
+      GroupParams p;
+      p.mn = __shfl(mine.mn, src);
+      p.scale = __shfl(mine.scale, src);
+      p.top = __shfl(mine.top, src);
+      return [p](int) -> const GroupParams& { return p; };
+    };
     if (any_fix)
-      decode_rows<DT, BITS, true>(vcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0, n,
-                                  param_of_row);
+      decode_rows<DT, BITS, true>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
     else
-      decode_rows<DT, BITS, false>(vcodes, geo.row_bytes, lane_code_off, dst, a.token_stride, lane_dst_off, rows, t0,
-                                   n, param_of_row);
+      decode_rows<DT, BITS, false>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
   }
 }
 
-__device__ __forceinline__ bool header_matches(const uint8_t* blob, int dt, int bits, int l, int n, int c,
-                                               size_t total) {
-  uintx4 a = gload<uintx4>(blob), b = gload<uintx4>(blob + 16);
-  return a.x == kMagic && a.y == (1u | (uint32_t)dt << 16 | (uint32_t)bits << 24) && a.z == (uint32_t)l &&
-         a.w == (uint32_t)n && b.x == (uint32_t)c && b.y == ((uint32_t)kGroup | (uint32_t)kGroup << 16) &&
-         b.z == (uint32_t)total && b.w == (uint32_t)((uint64_t)total >> 32);
-}
-
-// grid = (ceil(units / 4), 2 * l, items); unit = (16-row tile, strip), strip fastest, one per wave.
+// grid = (ceil(units / waves per block), 2 * l, items); unit = (16-row tile, strip), strip fastest, one per wave.
 template <int DT>
-__global__ __launch_bounds__(kBlockThreads) void decode_kernel(DecodeParams a) {
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
   kvh_item it;
   if (a.items != nullptr) {
@@ -250,38 +290,31 @@ __global__ __launch_bounds__(kBlockThreads) void decode_kernel(DecodeParams a) {
   }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
-  const int unit = blockIdx.x * kWavesPerBlock + wave;
+  const int unit = blockIdx.x * kDecWaves + wave;
   const int tile = unit / nstrips;
   const int strip = unit - tile * nstrips;
   const int t0 = tile * kDecRows;
   if (it.n_tokens < 1 || t0 >= it.n_tokens) return;
-  const int bits = level_bits(it.level);
-  const uint8_t* blob = static_cast<const uint8_t*>(it.blob);
-  bool ok = bits > 0;
-  LayerGeom geo = layer_geom(it.n_tokens, a.c, ok ? bits : 8);
-  if (ok) ok = header_matches(blob, DT, bits, a.l, it.n_tokens, a.c, kHeaderBytes + (size_t)a.l * geo.layer_bytes());
-  if (!ok) {
-    if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
-    return;
-  }
   const int lam = blockIdx.y >> 1;
   const bool is_v = blockIdx.y & 1;
-  const uint8_t* layer_base = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
-  switch (bits) {
-    case 8: decode_unit<DT, 8>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
-    case 4: decode_unit<DT, 4>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
-    default: decode_unit<DT, 2>(a, it, layer_base, geo, lam, is_v, t0, strip); break;
+  switch (it.level) {
+    case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip); break;
+    case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip); break;
+    case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip); break;
+    default:
+      if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
+      break;
   }
 }
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
   const int64_t units = (int64_t)((max_tokens + kDecRows - 1) / kDecRows) * nstrips;
-  dim3 grid((unsigned)((units + kWavesPerBlock - 1) / kWavesPerBlock), (unsigned)(2 * a.l), (unsigned)n_items);
+  dim3 grid((unsigned)((units + kDecWaves - 1) / kDecWaves), (unsigned)(2 * a.l), (unsigned)n_items);
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kBlockThreads), 0, stream, a);
+    hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, a);
   else
-    hipLaunchKernelGGL(decode_kernel<KVH_BF16>, grid, dim3(kBlockThreads), 0, stream, a);
+    hipLaunchKernelGGL(decode_kernel<KVH_BF16>, grid, dim3(kDecThreads), 0, stream, a);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }
