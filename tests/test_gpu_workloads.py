@@ -1,0 +1,204 @@
+"""GPU parity at the full sizes of the five workload configurations, in the launch
+configuration the benchmark times (batched launches over 256/512-token chunks).
+
+Configs 1 and 2 are compared with the oracle in full.  Configs 3-5 are too large for the host,
+so a spread of chunks (first, last, ragged tails included) is copied back and compared with the
+oracle byte for byte, and the rest is covered by properties that hold at any size: clean status
+words, exact idempotence of re-encoding on the device, and agreement between the batched,
+streamed, contiguous and paged code paths.
+"""
+import concurrent.futures as cf
+import os
+
+import numpy as np
+import pytest
+
+import kv_inputs as gen
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = gen.F16, gen.BF16
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def kvh():
+    import paper_2509_00105_amd as m
+
+    m.lib()
+    return m
+
+
+def bits(t):
+    """device 16-bit tensor -> host uint16 array"""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def chunk_plan(kvh, l, N, c, chunk, level_of_chunk):
+    spans = [(t0, min(chunk, N - t0)) for t0 in range(0, N, chunk)]
+    levels = [level_of_chunk(i) for i in range(len(spans))]
+    sizes = [kvh.blob_size(l, n, c, lv) for (_, n), lv in zip(spans, levels)]
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+    return spans, levels, sizes, offs
+
+
+def encode_all(kvh, kv, spans, levels, sizes, offs, chunk, token_base=0):
+    blobs = torch.empty(int(sum(sizes)), dtype=torch.uint8, device="cuda")
+    items = kvh.make_enc_items([blobs.data_ptr() + int(o) for o in offs], [token_base + t0 for t0, _ in spans],
+                               [n for _, n in spans], levels, "cuda")
+    kvh.encode_batch(items, len(spans), chunk, kv[0], kv[1])
+    return blobs
+
+
+def decode_all(kvh, blobs, spans, levels, offs, chunk, out, token_base=0):
+    status = torch.zeros(len(spans), dtype=torch.int32, device="cuda")
+    items = kvh.make_dec_items([blobs.data_ptr() + int(o) for o in offs], [n for _, n in spans], levels,
+                               [token_base + t0 for t0, _ in spans], [0] * len(spans), "cuda")
+    kvh.decode_batch(items, len(spans), chunk, out[0], out[1], status=status)
+    torch.cuda.synchronize()
+    assert int(status.abs().sum().item()) == 0
+    return out
+
+
+def oracle_check_chunks(kv, out, blobs, picks, spans, levels, sizes, offs, dt, l, c, token_base=0):
+    """Copy the picked chunks back and compare blob bytes and decoded bits with the oracle (threaded)."""
+    jobs = []
+    for i in picks:
+        t0, n = spans[i]
+        src = bits(kv[:, :, token_base + t0:token_base + t0 + n])
+        got_blob = blobs[int(offs[i]):int(offs[i]) + sizes[i]].cpu().numpy()
+        got_out = bits(out[:, :, token_base + t0:token_base + t0 + n]) if out is not None else None
+        jobs.append((i, n, levels[i], src, got_blob, got_out))
+
+    def run(job):
+        i, n, level, src, got_blob, got_out = job
+        want = oracle.encode(src[0], src[1], dt, level)
+        if not np.array_equal(want, got_blob):
+            return "chunk %d level %d: blob differs from the oracle" % (i, level)
+        if got_out is not None:
+            wk, wv = oracle.decode(want, dt, l, n, c, level)
+            if not (np.array_equal(wk, got_out[0]) and np.array_equal(wv, got_out[1])):
+                return "chunk %d level %d: decoded values differ from the oracle" % (i, level)
+        return None
+
+    with cf.ThreadPoolExecutor(max_workers=THREADS) as ex:
+        errs = [e for e in ex.map(run, jobs) if e]
+    assert not errs, errs
+
+
+def test_config1_tiny_full_parity_and_invariants(kvh):
+    cfg = gen.CONFIGS["tiny"]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    k, v = gen.make_kv(l, N, c, dt, cfg.seed)
+    kv = torch.stack([torch.from_numpy(k.view(np.int16)).cuda(), torch.from_numpy(v.view(np.int16)).cuda()]).view(torch.float16)
+    errs = []
+    for level in range(3):
+        spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: level)
+        blobs = encode_all(kvh, kv, spans, levels, sizes, offs, chunk)
+        out = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.zeros_like(kv))
+        oracle_check_chunks(kv, out, blobs, range(len(spans)), spans, levels, sizes, offs, dt, l, c)
+        # idempotence, on the device
+        again = encode_all(kvh, out, spans, levels, sizes, offs, chunk)
+        torch.cuda.synchronize()
+        assert torch.equal(blobs, again)
+        e = (out.float() - kv.float())
+        errs.append((float(e.pow(2).mean().sqrt()), float(e.abs().max())))
+    assert errs[0][0] <= errs[1][0] <= errs[2][0] and errs[0][1] <= errs[1][1] <= errs[2][1]
+
+
+def test_config2_llama3_8b_full_parity_in_bench_configuration(kvh):
+    cfg = gen.CONFIGS["llama3_8b_8k"]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    kv = gen.make_kv_device(l, N, c, dt, cfg.seed)
+    for level in range(3):
+        spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: level)
+        blobs = encode_all(kvh, kv, spans, levels, sizes, offs, chunk)
+        out = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.zeros_like(kv))
+        oracle_check_chunks(kv, out, blobs, range(len(spans)), spans, levels, sizes, offs, dt, l, c)
+
+
+def test_config3_llama3_70b_sampled_parity_and_idempotence(kvh):
+    cfg = gen.CONFIGS["llama3_70b_32k"]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    kv = gen.make_kv_device(l, N, c, dt, cfg.seed, drift=True)
+    out = torch.empty_like(kv)
+    n_chunks = N // chunk
+    picks = [0, 21, 42, n_chunks - 1]
+    for level in range(3):
+        spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: level)
+        blobs = encode_all(kvh, kv, spans, levels, sizes, offs, chunk)
+        decode_all(kvh, blobs, spans, levels, offs, chunk, out)
+        oracle_check_chunks(kv, out, blobs, picks[level:level + 2] if level else picks[:2], spans, levels, sizes, offs, dt, l, c)
+        again = encode_all(kvh, out, spans, levels, sizes, offs, chunk)
+        torch.cuda.synchronize()
+        assert torch.equal(blobs, again), "re-encoding the decoded tensor changed the blobs at level %d" % level
+        del blobs, again
+
+
+def test_config4_long_context_streamed_decode(kvh):
+    cfg = gen.CONFIGS["long_7b_128k"]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    kv = gen.make_kv_device(l, N, c, dt, cfg.seed)
+    n_chunks = N // chunk
+    for level in (0, 2):
+        spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: level)
+        blobs = torch.empty(int(sum(sizes)), dtype=torch.uint8, device="cuda")
+        kvh.encode_chunked(kv[0], kv[1], chunk, levels, blobs, offs)       # one launch per chunk, one stream
+        batched = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.empty_like(kv))
+        streamed = torch.empty_like(kv)
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for i, (t0, n) in enumerate(spans):                                 # chunk by chunk, never synchronising
+            kvh.decode(blobs[int(offs[i]):int(offs[i]) + sizes[i]], level, n, streamed[0], streamed[1], dst_token0=t0,
+                       status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        assert torch.equal(streamed.view(torch.int16), batched.view(torch.int16))
+        oracle_check_chunks(kv, streamed, blobs, [0, 255, n_chunks - 1], spans, levels, sizes, offs, dt, l, c)
+        del blobs, batched, streamed
+
+
+def test_config5_mixed_batch_paged_decode(kvh):
+    dt, l, c, chunk, bt = BF16, 32, 1024, 256, 16
+    lengths = gen.mixed_batch_lengths()
+    chunks, tables, n_pages = gen.mixed_batch_plan(lengths, chunk, bt)
+    total = int(lengths.sum())
+    starts = np.concatenate([[0], np.cumsum(lengths)[:-1]]).astype(np.int64)
+    assert 64 == len(lengths) and lengths.min() >= 256 and lengths.max() <= 32768
+    kv = gen.make_kv_device(l, total, c, dt, seed=4)                        # all requests back to back
+    # encode every chunk of every request at its own level (one launch)
+    req = [r for r, _, _, _ in chunks]
+    spans = [(int(starts[r] + t0), n) for r, t0, n, _ in chunks]
+    levels = [lv for _, _, _, lv in chunks]
+    sizes = [kvh.blob_size(l, n, c, lv) for (_, n), lv in zip(spans, levels)]
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+    blobs = encode_all(kvh, kv, spans, levels, sizes, offs, chunk)
+    # paged decode: one launch, each item carries its request's page table
+    table_dev = torch.from_numpy(np.concatenate(tables)).cuda()
+    table_start = np.concatenate([[0], np.cumsum([len(t) for t in tables])[:-1]])
+    paged = torch.zeros((2, l, n_pages, bt, c), dtype=torch.bfloat16, device="cuda")
+    status = torch.zeros(len(chunks), dtype=torch.int32, device="cuda")
+    items = kvh.make_dec_items([blobs.data_ptr() + int(o) for o in offs], [n for _, n in spans], levels,
+                               [t0 for _, t0, _, _ in chunks],
+                               [table_dev.data_ptr() + 4 * int(table_start[r]) for r in req], "cuda")
+    kvh.decode_batch(items, len(chunks), chunk, paged[0], paged[1], paged=True, block_tokens=bt, status=status)
+    torch.cuda.synchronize()
+    assert int(status.abs().sum().item()) == 0
+    # contiguous decode of the same blobs, then gather the paged cache back into logical order: must agree everywhere
+    contiguous = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.empty_like(kv))
+    for r in range(len(lengths)):
+        n = int(lengths[r])
+        tab = torch.from_numpy(tables[r].astype(np.int64)).cuda()
+        got = paged[:, :, tab].reshape(2, l, -1, c)[:, :, :n]
+        assert torch.equal(got.view(torch.int16), contiguous[:, :, int(starts[r]):int(starts[r]) + n].view(torch.int16)), r
+    # no page outside the requests' tokens was written
+    used = torch.zeros(n_pages * bt, dtype=torch.bool, device="cuda")
+    for r in range(len(lengths)):
+        s = torch.arange(int(lengths[r]), device="cuda")
+        used[torch.from_numpy(tables[r].astype(np.int64)).cuda()[s // bt] * bt + s % bt] = True
+    assert not paged.view(2, l, n_pages * bt, c)[:, :, ~used].any()
+    # oracle on a spread of chunks, ragged tails first
+    ragged = [i for i, (_, n) in enumerate(spans) if n % 128][:3]
+    picks = sorted(set(ragged + [0, len(spans) // 2, len(spans) - 1]))
+    oracle_check_chunks(kv, contiguous, blobs, picks, spans, levels, sizes, offs, dt, l, c)
