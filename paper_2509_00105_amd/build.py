@@ -10,9 +10,11 @@ LIB = os.path.join(HERE, "libkvh.so")
 SOURCES = ["kvh_api.hip", "kvh_decode.hip", "kvh_encode.hip"]
 
 # -ffp-contract=off: the codec's arithmetic fuses only where the source says fma.
+# -fno-honor-nans: inputs are finite by contract; without it every min/max of a value unpacked with
+# integer ops is preceded by a canonicalising v_max (sNaN quieting).
 # packed-fp32-ops off: hipcc must not form v_pk_*_f32 from the scalar float code.
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-fno-honor-nans",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 

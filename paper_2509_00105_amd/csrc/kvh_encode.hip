@@ -7,7 +7,9 @@
 //     reduces its rows per channel, the 8 partial results meet in LDS, then every wave
 //     quantises its own registers.
 //   V (statistics over the 128 channels of a head): a head is 16 lanes x 8 channels, reduced
-//     with a 4-step butterfly inside the wave.
+//     with a 4-step rotate-and-combine inside the 16-lane DPP row.
+// Quantised codes are produced with the packed float->u8 convert, which rounds to nearest even
+// and inserts the byte in one instruction; narrower codes are then squeezed out of the bytes.
 #include "kvh_common.hpp"
 
 namespace kvh {
@@ -18,13 +20,30 @@ constexpr int kEncRows = 16;                          // rows per wave
 constexpr int kEncTile = kEncRows * kEncWaves;        // 128 tokens per block = one K group
 static_assert(kEncTile == kGroup, "a K block must cover exactly one token-group");
 
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+template <typename T>
+__device__ __forceinline__ T gload(const void* p) {
+  return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+template <typename T>
+__device__ __forceinline__ void gstore(void* p, T v) {
+  *reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)) = v;
+}
+
 template <int DT>
-__device__ __forceinline__ void unpack8(const uint4& d, float (&x)[8]) {
+__device__ __forceinline__ void unpack8(const uintx4& d, float (&x)[8]) {
   const uint32_t w[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    x[2 * j] = t16_to_f32<DT>(w[j] & 0xffffu);
-    x[2 * j + 1] = t16_to_f32<DT>(w[j] >> 16);
+    if constexpr (DT == KVH_F16) {
+      x[2 * j] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[j] & 0xffffu));
+      x[2 * j + 1] = (float)__builtin_bit_cast(_Float16, (uint16_t)(w[j] >> 16));
+    } else {
+      x[2 * j] = __builtin_bit_cast(float, w[j] << 16);
+      x[2 * j + 1] = __builtin_bit_cast(float, w[j] & 0xffff0000u);
+    }
   }
 }
 
@@ -40,31 +59,45 @@ __device__ __forceinline__ uint32_t exact_bits(float f) {
   return b == 0x8000u ? 0u : b;
 }
 
-template <int BITS>
-__device__ __forceinline__ uint32_t quantise1(float x, float mn, float inv) {
-  constexpr float L = float((1 << BITS) - 1);
-  float t = (x - mn) * inv;                 // two roundings: compiled with -ffp-contract=off
-  float r = __builtin_rintf(t);             // v_rndne_f32: ties to even
-  r = __builtin_fminf(__builtin_fmaxf(r, 0.0f), L);
-  return (uint32_t)r;
+// t = (x - mn) * inv: two roundings (the file is compiled with -ffp-contract=off).  For finite
+// input 0 <= t <= L * (1 + 2^-23), so rounding to nearest even never leaves [0, L].
+__device__ __forceinline__ float position(float x, float mn, float inv) { return (x - mn) * inv; }
+
+// Four positions -> four code bytes in one word (byte j = code j).  The convert rounds to
+// nearest even and saturates to [0, 255].
+__device__ __forceinline__ uint32_t codes4(float t0, float t1, float t2, float t3) {
+  uint32_t a = __builtin_amdgcn_cvt_pk_u8_f32(t0, 0, 0u);
+  a = __builtin_amdgcn_cvt_pk_u8_f32(t1, 1, a);
+  a = __builtin_amdgcn_cvt_pk_u8_f32(t2, 2, a);
+  return __builtin_amdgcn_cvt_pk_u8_f32(t3, 3, a);
 }
 
-// Pack 8 codes LSB-first and store the BITS bytes they occupy.
-template <int BITS>
-__device__ __forceinline__ void store_codes(uint8_t* p, const uint32_t (&q)[8]) {
+// Quantise 8 elements and store the BITS bytes they occupy (LSB-first packing).
+// param(j) returns {mn, inv} of channel j.
+template <int BITS, typename P>
+__device__ __forceinline__ void quantise_store8(uint8_t* p, const float (&x)[8], P&& param) {
+  float t[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) t[j] = position(x[j], param(j).x, param(j).y);
+  uint32_t a = codes4(t[0], t[1], t[2], t[3]);
+  uint32_t b = codes4(t[4], t[5], t[6], t[7]);
   if constexpr (BITS == 8) {
-    uint2 w = {q[0] | q[1] << 8 | q[2] << 16 | q[3] << 24, q[4] | q[5] << 8 | q[6] << 16 | q[7] << 24};
-    *reinterpret_cast<uint2*>(p) = w;
+    uintx2 w = {a, b};
+    gstore<uintx2>(p, w);
   } else if constexpr (BITS == 4) {
-    uint32_t w = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) w |= q[j] << (4 * j);
-    *reinterpret_cast<uint32_t*>(p) = w;
+    a &= 0x0f0f0f0fu;  // no-ops for finite input; keep stray bits of unspecified codes inside their field
+    b &= 0x0f0f0f0fu;
+    a |= a >> 4;       // byte 0 = c0 | c1 << 4, byte 2 = c2 | c3 << 4
+    b |= b >> 4;
+    gstore<uint32_t>(p, __builtin_amdgcn_perm(b, a, 0x06040200u));
   } else {
-    uint32_t w = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) w |= q[j] << (2 * j);
-    *reinterpret_cast<uint16_t*>(p) = (uint16_t)w;
+    a &= 0x03030303u;
+    b &= 0x03030303u;
+    a |= a >> 6;       // byte 0 = c0 | c1 << 2, byte 2 = c2 | c3 << 2
+    b |= b >> 6;
+    a |= a >> 12;      // byte 0 = c0 | c1 << 2 | c2 << 4 | c3 << 6
+    b |= b >> 12;
+    gstore<uint16_t>(p, (uint16_t)__builtin_amdgcn_perm(b, a, 0x0c0c0400u));
   }
 }
 
@@ -72,40 +105,48 @@ template <int DT, int BITS>
 __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_enc_item& it, uint8_t* layer_base,
                                                const LayerGeom& geo, int lam, int g, int strip, float* red) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = it.n_tokens;
   const int c = a.c;
-  const int ch0 = strip * kStripCh + lane * kLaneCh;
-  const bool active = ch0 < c;
+  const int ch_raw = strip * kStripCh + lane * kLaneCh;
+  const bool active = ch_raw < c;
+  const int ch0 = active ? ch_raw : 0;  // idle lanes of a partial strip shadow lane 0 and never store
   const int t_first = g * kGroup + wave * kEncRows;
-  const uint16_t* src = a.k + (int64_t)lam * a.layer_stride + ch0;
+  const uint8_t* src = reinterpret_cast<const uint8_t*>(a.k + (int64_t)lam * a.layer_stride);  // wave-uniform
+  const uint32_t lane_src_off = (uint32_t)ch0 * 2u;
 
   // Rows past the end of the blob re-read its last row: a duplicate never changes a min or max.
-  uint4 d[kEncRows];
-  if (active) {
+  uintx4 d[kEncRows];
 #pragma unroll
-    for (int i = 0; i < kEncRows; ++i) {
-      int t = t_first + i;
-      t = t < n ? t : n - 1;
-      d[i] = *reinterpret_cast<const uint4*>(src + (it.src_token0 + t) * a.token_stride);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < kEncRows; ++i) d[i] = make_uint4(0, 0, 0, 0);
+  for (int i = 0; i < kEncRows; ++i) {
+    int t = t_first + i;
+    t = t < n ? t : n - 1;
+    d[i] = gload<uintx4>(src + (it.src_token0 + t) * a.token_stride * 2 + lane_src_off);
   }
   float mn[8], mx[8];
   unpack8<DT>(d[0], mn);
 #pragma unroll
   for (int j = 0; j < 8; ++j) mx[j] = mn[j];
-#pragma unroll
-  for (int i = 1; i < kEncRows; ++i) {
-    float x[8];
-    unpack8<DT>(d[i], x);
+  {
+    float x1[8];
+    unpack8<DT>(d[1], x1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      mn[j] = __builtin_fminf(mn[j], x[j]);
-      mx[j] = __builtin_fmaxf(mx[j], x[j]);
+      mn[j] = __builtin_fminf(mn[j], x1[j]);
+      mx[j] = __builtin_fmaxf(mx[j], x1[j]);
     }
+  }
+#pragma unroll
+  for (int i = 2; i < kEncRows; i += 2) {  // two rows per step: three-operand min / max
+    float x0[8], x1[8];
+    unpack8<DT>(d[i], x0);
+    unpack8<DT>(d[i + 1], x1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      mn[j] = __builtin_fminf(__builtin_fminf(mn[j], x0[j]), x1[j]);
+      mx[j] = __builtin_fmaxf(__builtin_fmaxf(mx[j], x0[j]), x1[j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the unpacked floats of different rows from piling up in registers
   }
   // red[0][wave][512] = partial minima, red[1][wave][512] = partial maxima
   float* rmn = red + (0 * kEncWaves + wave) * kStripCh + lane * kLaneCh;
@@ -115,6 +156,14 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
   *reinterpret_cast<float4*>(rmx) = make_float4(mx[0], mx[1], mx[2], mx[3]);
   *reinterpret_cast<float4*>(rmx + 4) = make_float4(mx[4], mx[5], mx[6], mx[7]);
   __syncthreads();
+  // The rows are unpacked a second time for quantisation.  Hide them from common-subexpression
+  // elimination, or the compiler keeps all 128 unpacked floats alive across the barrier.
+#pragma unroll
+  for (int i = 0; i < kEncRows; ++i) {
+    uint32_t w0 = d[i].x, w1 = d[i].y, w2 = d[i].z, w3 = d[i].w;
+    asm volatile("" : "+v"(w0), "+v"(w1), "+v"(w2), "+v"(w3));
+    d[i] = uintx4{w0, w1, w2, w3};
+  }
 #pragma unroll
   for (int w = 0; w < kEncWaves; ++w) {
     const float* pmn = red + (0 * kEncWaves + w) * kStripCh + lane * kLaneCh;
@@ -129,35 +178,52 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
       mx[j] = __builtin_fmaxf(mx[j], bm[j]);
     }
   }
-  if (!active) return;
 
   uint32_t meta[8];
-  float inv[8];
+  float2 par[8];  // {mn, inv}
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     uint32_t lo = exact_bits<DT>(mn[j]), hi = exact_bits<DT>(mx[j]);
     meta[j] = lo | hi << 16;
-    mn[j] = t16_to_f32<DT>(lo);
-    inv[j] = encode_inv<BITS>(mn[j], t16_to_f32<DT>(hi));
+    par[j].x = t16_to_f32<DT>(lo);
+    par[j].y = encode_inv<BITS>(par[j].x, t16_to_f32<DT>(hi));
   }
+  if (!active) return;
   if (wave == 0) {
-    uint4* mp = reinterpret_cast<uint4*>(layer_base + ((size_t)g * c + ch0) * 4);
-    mp[0] = make_uint4(meta[0], meta[1], meta[2], meta[3]);
-    mp[1] = make_uint4(meta[4], meta[5], meta[6], meta[7]);
+    uint8_t* mp = layer_base + ((size_t)g * c + ch0) * 4;
+    uintx4 m0 = {meta[0], meta[1], meta[2], meta[3]}, m1 = {meta[4], meta[5], meta[6], meta[7]};
+    gstore<uintx4>(mp, m0);
+    gstore<uintx4>(mp + 16, m1);
   }
-  uint8_t* codes = layer_base + geo.kmeta + (size_t)ch0 * BITS / 8;
+  uint8_t* codes = layer_base + geo.kmeta;  // wave-uniform
+  const uint32_t lane_code_off = (uint32_t)ch0 * BITS / 8;
 #pragma unroll
   for (int i = 0; i < kEncRows; ++i) {
     int t = t_first + i;
-    if (t < n) {
+    if (t < n) {  // wave-uniform
       float x[8];
-      uint32_t q[8];
       unpack8<DT>(d[i], x);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) q[j] = quantise1<BITS>(x[j], mn[j], inv[j]);
-      store_codes<BITS>(codes + (size_t)t * geo.row_bytes, q);
+      quantise_store8<BITS>(codes + (size_t)t * geo.row_bytes + lane_code_off, x, [&](int j) { return par[j]; });
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+// all-reduce over the 16 lanes of a DPP row (= one head): rotate by 8, 4, 2, 1 and combine
+template <bool IS_MIN>
+__device__ __forceinline__ float row16_reduce(float v) {
+#define KVH_ROR_STEP(CTRL)                                                                          \
+  {                                                                                                 \
+    float o = __builtin_bit_cast(                                                                   \
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false)); \
+    v = IS_MIN ? __builtin_fminf(v, o) : __builtin_fmaxf(v, o);                                     \
+  }
+  KVH_ROR_STEP(0x128)  // row_ror:8
+  KVH_ROR_STEP(0x124)  // row_ror:4
+  KVH_ROR_STEP(0x122)  // row_ror:2
+  KVH_ROR_STEP(0x121)  // row_ror:1
+#undef KVH_ROR_STEP
+  return v;
 }
 
 template <int DT, int BITS>
@@ -165,70 +231,74 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
                                                const LayerGeom& geo, int lam, int tile, int strip) {
   constexpr int kBatch = 8;  // rows in flight per wave
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = it.n_tokens;
   const int c = a.c;
   const int heads = c / kGroup;
-  const int ch0 = strip * kStripCh + lane * kLaneCh;
-  const bool active = ch0 < c;
+  const int ch_raw = strip * kStripCh + lane * kLaneCh;
+  const bool active = ch_raw < c;  // uniform over the 16 lanes of a head
+  const int ch0 = active ? ch_raw : 0;
   const int t_first = tile * kEncTile + wave * kEncRows;
-  const uint16_t* src = a.v + (int64_t)lam * a.layer_stride + (active ? ch0 : 0);
+  const uint8_t* src = reinterpret_cast<const uint8_t*>(a.v + (int64_t)lam * a.layer_stride);  // wave-uniform
+  const uint32_t lane_src_off = (uint32_t)ch0 * 2u;
   uint8_t* vmeta = layer_base + geo.kmeta + geo.codes;
-  uint8_t* codes = vmeta + geo.vmeta + (size_t)ch0 * BITS / 8;
+  uint8_t* codes = vmeta + geo.vmeta;  // wave-uniform
+  const uint32_t lane_code_off = (uint32_t)ch0 * BITS / 8;
 
   for (int i0 = 0; i0 < kEncRows; i0 += kBatch) {
     if (t_first + i0 >= n) break;  // wave-uniform
-    uint4 d[kBatch];
+    uintx4 d[kBatch];
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
       int t = t_first + i0 + i;
       t = t < n ? t : n - 1;
-      // lanes beyond c re-read the row's first channels; their results are never stored
-      d[i] = *reinterpret_cast<const uint4*>(src + (it.src_token0 + t) * a.token_stride);
+      d[i] = gload<uintx4>(src + (it.src_token0 + t) * a.token_stride * 2 + lane_src_off);
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
       int t = t_first + i0 + i;
       float x[8];
       unpack8<DT>(d[i], x);
-      float mn = x[0], mx = x[0];
-#pragma unroll
-      for (int j = 1; j < 8; ++j) {
-        mn = __builtin_fminf(mn, x[j]);
-        mx = __builtin_fmaxf(mx, x[j]);
-      }
-#pragma unroll
-      for (int m = 1; m < 16; m <<= 1) {  // butterfly over the 16 lanes of a head
-        mn = __builtin_fminf(mn, __shfl_xor(mn, m));
-        mx = __builtin_fmaxf(mx, __shfl_xor(mx, m));
-      }
+      float mn = __builtin_fminf(__builtin_fminf(x[0], x[1]), x[2]);
+      float mx = __builtin_fmaxf(__builtin_fmaxf(x[0], x[1]), x[2]);
+      mn = __builtin_fminf(__builtin_fminf(mn, x[3]), x[4]);
+      mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[3]), x[4]);
+      mn = __builtin_fminf(__builtin_fminf(mn, x[5]), x[6]);
+      mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[5]), x[6]);
+      mn = __builtin_fminf(mn, x[7]);
+      mx = __builtin_fmaxf(mx, x[7]);
+      mn = row16_reduce<true>(mn);
+      mx = row16_reduce<false>(mx);
       if (active && t < n) {
         uint32_t lo = exact_bits<DT>(mn), hi = exact_bits<DT>(mx);
-        if ((lane & 15) == 0)
-          *reinterpret_cast<uint32_t*>(vmeta + ((size_t)t * heads + (ch0 / kGroup)) * 4) = lo | hi << 16;
-        float fmn = t16_to_f32<DT>(lo);
-        float inv = encode_inv<BITS>(fmn, t16_to_f32<DT>(hi));
-        uint32_t q[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) q[j] = quantise1<BITS>(x[j], fmn, inv);
-        store_codes<BITS>(codes + (size_t)t * geo.row_bytes, q);
+        if ((lane & 15) == 0) gstore<uint32_t>(vmeta + ((size_t)t * heads + (ch0 / kGroup)) * 4, lo | hi << 16);
+        float2 par;
+        par.x = t16_to_f32<DT>(lo);
+        par.y = encode_inv<BITS>(par.x, t16_to_f32<DT>(hi));
+        quantise_store8<BITS>(codes + (size_t)t * geo.row_bytes + lane_code_off, x, [&](int) { return par; });
       }
     }
   }
   // zero the padding that rounds the vmeta section up to 16 bytes
   if (strip == 0 && threadIdx.x == 0 && (tile + 1) * kEncTile >= n) {
     size_t used = (size_t)n * heads * 4;
-    for (size_t o = used; o < geo.vmeta; o += 4) *reinterpret_cast<uint32_t*>(vmeta + o) = 0u;
+    for (size_t o = used; o < geo.vmeta; o += 4) gstore<uint32_t>(vmeta + o, 0u);
   }
 }
 
 // grid = (token-groups x strips, 2 * l, items)
 template <int DT>
-__global__ __launch_bounds__(kEncThreads) void encode_kernel(EncodeParams a) {
+__global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void encode_kernel(EncodeParams a) {
   __shared__ float red[2 * kEncWaves * kStripCh];  // 32 KiB
   kvh_enc_item it;
   if (a.items != nullptr) {
-    it = a.items[blockIdx.z];
+    const kvh_enc_item* p = a.items + blockIdx.z;
+    uintx4 lo = gload<uintx4>(p);
+    uintx2 hi = gload<uintx2>(reinterpret_cast<const uint8_t*>(p) + 16);
+    it.blob = reinterpret_cast<void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
+    it.src_token0 = (int64_t)((uint64_t)lo.z | (uint64_t)lo.w << 32);
+    it.n_tokens = (int32_t)hi.x;
+    it.level = (int32_t)hi.y;
   } else {
     it = a.one;
   }
@@ -256,7 +326,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(EncodeParams a) {
       case 7: w = (uint32_t)(total >> 32); break;
       default: break;
     }
-    reinterpret_cast<uint32_t*>(blob)[threadIdx.x] = w;
+    gstore<uint32_t>(blob + 4 * threadIdx.x, w);
   }
   uint8_t* layer_base = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
   if (!is_v) {
