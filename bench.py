@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_8k", choices=["llama3_8b_8k", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--cpu-sample-chunks", type=int, default=8)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=16)
     return ap.parse_args()
 
 
@@ -140,6 +140,19 @@ def main():
         wall = time.perf_counter() - t0
 
     assert all(int(status[lv].abs().sum().item()) == 0 for lv in range(3)), "a decode reported a header mismatch"
+
+    # Outside the timed region: the plain copy kernel over 1 GiB.  It gives the practical copy rate of
+    # this device next to the codec's figures, and a dispatch of known size for scaling HBM counters.
+    with torch.cuda.stream(stream):
+        probe_src, probe_dst = kv.view(torch.uint8).reshape(-1)[: 1 << 30], out.view(torch.uint8).reshape(-1)[: 1 << 30]
+        pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        kvh.copy_probe(probe_dst, probe_src, stream=stream)
+        pe[0].record(stream)
+        for _ in range(5):
+            kvh.copy_probe(probe_dst, probe_src, stream=stream)
+        pe[1].record(stream)
+        torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / pe[0].elapsed_time(pe[1]) / 1e6
     step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
@@ -173,6 +186,7 @@ def main():
                      "frac": dominant["hbm_frac"], "traffic": None},
         "decode_hbm_frac": {str(r["bits"]): r["hbm_frac"] for r in dec2},
         "kernels": per_kernel,
+        "copy_probe_GBps": copy_gbps,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),
     }

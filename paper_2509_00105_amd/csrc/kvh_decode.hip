@@ -3,12 +3,15 @@
 // overhead the paper's estimator profiles; Design section).
 //
 // Pure streaming kernel, no LDS and no block-level cooperation: the unit of work is one wave
-// decoding 16 consecutive token rows of one 512-channel strip.  A lane owns 8 channels, so each
-// store is one 128-bit access and the wave writes 1 KiB of a row per instruction.  K metadata
+// decoding 8 consecutive token rows of a 1024-channel span (two 512-channel segments), i.e. 16 KiB
+// of contiguous output when c = 1024.  A lane owns 8 channels per segment, so each store is one
+// 128-bit access and the wave writes 1 KiB of a row per instruction.  K metadata
 // (per channel) is turned into fp32 parameters once per unit and stays in registers; V
 // metadata (per token and head) is prepared by one lane per group and broadcast.  The rare
 // groups whose top code does not land exactly on the stored maximum select a slower row loop
 // through a wave-uniform branch.
+#include <type_traits>
+
 #include "kvh_common.hpp"
 
 namespace kvh {
@@ -20,17 +23,22 @@ namespace kvh {
 #define KVH_DEC_NTL 0  // non-temporal loads of the packed codes
 #endif
 #ifndef KVH_DEC_WAVES
-#define KVH_DEC_WAVES 4  // waves per block (waves are independent; this only shapes dispatch)
+#define KVH_DEC_WAVES 8  // waves per block (waves are independent; this only shapes dispatch)
 #endif
 constexpr int kDecWaves = KVH_DEC_WAVES;
 constexpr int kDecThreads = kDecWaves * kWave;
 
-#ifndef KVH_DEC_ROWS
-#define KVH_DEC_ROWS 16
+#ifndef KVH_DEC_SWAP
+#define KVH_DEC_SWAP 0  // 1: grid = (units, items, 2l) so that consecutive blocks walk one layer's rows across chunks
 #endif
-constexpr int kDecRows = KVH_DEC_ROWS;  // token rows per wave
+#ifndef KVH_DEC_SEGS
+#define KVH_DEC_SEGS 2  // 512-channel segments per wave: 1 = half a 1024-channel row, 2 = the whole row
+#endif
+constexpr int kDecSegs = KVH_DEC_SEGS;
+constexpr int kDecSpanCh = kDecSegs * kStripCh;                 // channels covered by one wave
+constexpr int kDecHeads = kDecSpanCh / kGroup;                  // V groups per row of a unit
+constexpr int kDecRows = kWave / kDecHeads;                     // token rows per wave: one lane per V group
 static_assert(kGroup % kDecRows == 0, "a unit must not straddle K token-groups");
-static_assert(kDecRows * (kStripCh / kGroup) <= kWave, "one lane per (row, head) group of a unit");
 
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -142,20 +150,6 @@ __device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_t
   return gload<int32_t>(reinterpret_cast<const uint8_t*>(page_table + blk)) * block_tokens + (int32_t)(su - blk * bt);
 }
 
-// Compute and store the rows of one unit from codes already in registers.
-template <int DT, int BITS, bool FIX, typename P>
-__device__ __forceinline__ void decode_rows(const Codes<BITS> (&cw)[kDecRows], uint16_t* dst, int64_t token_stride,
-                                            uint32_t lane_dst_off, const int32_t (&rows)[kDecRows], int t0, int n,
-                                            bool active, P&& param_of_row) {
-#pragma unroll
-  for (int i = 0; i < kDecRows; ++i) {
-    if (t0 + i < n) {  // wave-uniform
-      uint4 out = dequant8<DT, BITS, FIX>(cw[i], param_of_row(i));
-      if (active) gstore16(dst + (int64_t)rows[i] * token_stride + lane_dst_off, out);
-    }
-  }
-}
-
 struct HeaderWords {
   uintx4 a, b;
 };
@@ -175,7 +169,7 @@ __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int
 // blob pointer, so these loads stay inside the buffer whatever the header says.
 template <int DT, int BITS>
 __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
-                                            int t0, int strip) {
+                                            int t0, int span) {
   const int lane = threadIdx.x & (kWave - 1);
   const int n = it.n_tokens;
   const int c = a.c;
@@ -183,9 +177,16 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   const LayerGeom geo = layer_geom(n, c, BITS);
   const HeaderWords hdr = load_header(blob);
 
-  const int ch_raw = strip * kStripCh + lane * kLaneCh;
-  const bool active = ch_raw < c;
-  const int ch0 = active ? ch_raw : 0;  // idle lanes of a partial strip shadow lane 0 and never store
+  // segment s of this lane: 8 channels starting at ch[s]; idle lanes of a partial span shadow
+  // channel 0 and never store
+  bool active[kDecSegs];
+  uint32_t ch[kDecSegs];
+#pragma unroll
+  for (int s = 0; s < kDecSegs; ++s) {
+    int raw = span * kDecSpanCh + s * kStripCh + lane * kLaneCh;
+    active[s] = raw < c;
+    ch[s] = active[s] ? (uint32_t)raw : 0u;
+  }
 
   // Row i's destination is computed by lane i, then handed to the whole wave as a scalar.
   int32_t my_row = 0;
@@ -199,30 +200,33 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   const uint8_t* vmeta = kcodes + geo.codes;
   const uint8_t* vcodes = vmeta + geo.vmeta;
   uint16_t* dst = (is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride;
-  const uint32_t lane_dst_off = (uint32_t)ch0;
-  const uint8_t* codes = (is_v ? vcodes : kcodes) + (uint32_t)ch0 * BITS / 8;
+  const uint8_t* codes = is_v ? vcodes : kcodes;
   const int heads = c / kGroup;
 
-  // metadata: K = 8 channels of this lane; V = group (row lane/4, head lane%4) of this unit
-  uintx4 m0 = {0, 0, 0, 0}, m1 = {0, 0, 0, 0};
+  // metadata: K = the lane's 8 channels per segment; V = group (row lane / H, head lane % H) of this unit
+  uintx4 km[kDecSegs][2];
   uint32_t vm = 0;
   bool v_owner = false;
   if (!is_v) {
-    const uint8_t* mp = kmeta + ((size_t)(t0 / kGroup) * c + ch0) * 4;
-    m0 = gload<uintx4>(mp);
-    m1 = gload<uintx4>(mp + 16);
+#pragma unroll
+    for (int s = 0; s < kDecSegs; ++s) {
+      const uint8_t* mp = kmeta + ((size_t)(t0 / kGroup) * c + ch[s]) * 4;
+      km[s][0] = gload<uintx4>(mp);
+      km[s][1] = gload<uintx4>(mp + 16);
+    }
   } else {
-    int t = t0 + (lane >> 2);
-    int head = strip * (kStripCh / kGroup) + (lane & 3);
-    v_owner = (lane >> 2) < kDecRows && t < n && head < heads;
+    int t = t0 + lane / kDecHeads;
+    int head = span * kDecHeads + lane % kDecHeads;
+    v_owner = t < n && head < heads;
     if (v_owner) vm = gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4);
   }
-  Codes<BITS> cw[kDecRows];
+  Codes<BITS> cw[kDecRows][kDecSegs];
 #pragma unroll
   for (int i = 0; i < kDecRows; ++i) {
     int t = t0 + i;
     t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
-    cw[i].load(codes + (size_t)t * geo.row_bytes);
+#pragma unroll
+    for (int s = 0; s < kDecSegs; ++s) cw[i][s].load(codes + (size_t)t * geo.row_bytes + ch[s] * BITS / 8);
   }
 
   if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes())) {
@@ -233,21 +237,40 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
 #pragma unroll
   for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
 
+  // the row loop, instantiated with and without the explicit top-code rule
+  auto run = [&](auto fix_tag, auto&& param_of) {
+    constexpr bool FIX = decltype(fix_tag)::value;
+#pragma unroll
+    for (int i = 0; i < kDecRows; ++i) {
+      if (t0 + i < n) {  // wave-uniform
+        uint16_t* row = dst + (int64_t)rows[i] * a.token_stride;
+#pragma unroll
+        for (int s = 0; s < kDecSegs; ++s) {
+          uint4 out = dequant8<DT, BITS, FIX>(cw[i][s], param_of(i, s));
+          if (active[s]) gstore16(row + ch[s], out);
+        }
+      }
+    }
+  };
+  using Yes = std::integral_constant<bool, true>;
+  using No = std::integral_constant<bool, false>;
+
   if (!is_v) {
-    const uint32_t meta[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-    GroupParams gp[kLaneCh];
+    GroupParams gp[kDecSegs][kLaneCh];
     bool fix = false;
 #pragma unroll
-    for (int j = 0; j < kLaneCh; ++j) {
-      gp[j] = decode_params<DT, BITS>(meta[j]);
-      fix |= top_needs_fix<DT, BITS>(gp[j]);
+    for (int s = 0; s < kDecSegs; ++s) {
+      const uint32_t meta[8] = {km[s][0].x, km[s][0].y, km[s][0].z, km[s][0].w,
+                                km[s][1].x, km[s][1].y, km[s][1].z, km[s][1].w};
+#pragma unroll
+      for (int j = 0; j < kLaneCh; ++j) {
+        gp[s][j] = decode_params<DT, BITS>(meta[j]);
+        fix |= top_needs_fix<DT, BITS>(gp[s][j]);
+      }
     }
     const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-    auto param_of_row = [&](int) { return [&](int j) -> const GroupParams& { return gp[j]; }; };
-    if (any_fix)
-      decode_rows<DT, BITS, true>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
-    else
-      decode_rows<DT, BITS, false>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
+    auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
+    if (any_fix) run(Yes{}, param_of); else run(No{}, param_of);
   } else {
     GroupParams mine = {0.0f, 0.0f, 0u};
     bool fix = false;
@@ -256,26 +279,24 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
       fix = top_needs_fix<DT, BITS>(mine);
     }
     const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-    // every row pulls its group's three values from the lane that prepared them
-    auto param_of_row = [&](int i) {
-      int src = i * 4 + (lane >> 4);
+    // every (row, segment) pulls its group's three values from the lane that prepared them
+    auto param_of = [&](int i, int s) {
+      int src = i * kDecHeads + s * (kStripCh / kGroup) + (lane >> 4);
       GroupParams p;
       p.mn = __shfl(mine.mn, src);
       p.scale = __shfl(mine.scale, src);
       p.top = __shfl(mine.top, src);
       return [p](int) -> const GroupParams& { return p; };
     };
-    if (any_fix)
-      decode_rows<DT, BITS, true>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
-    else
-      decode_rows<DT, BITS, false>(cw, dst, a.token_stride, lane_dst_off, rows, t0, n, active, param_of_row);
+    if (any_fix) run(Yes{}, param_of); else run(No{}, param_of);
   }
 }
 
-// grid = (ceil(units / waves per block), 2 * l, items); unit = (16-row tile, strip), strip fastest, one per wave.
+// grid = (ceil(units / waves per block), 2 * l, items); unit = (row tile, channel span), span fastest, one per wave.
 template <int DT>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
-  const int item_idx = blockIdx.z;
+  const int item_idx = KVH_DEC_SWAP ? blockIdx.y : blockIdx.z;
+  const int lay_kv = KVH_DEC_SWAP ? blockIdx.z : blockIdx.y;
   kvh_item it;
   if (a.items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
@@ -289,14 +310,14 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
     it = a.one;
   }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nstrips = (a.c + kStripCh - 1) / kStripCh;
+  const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
   const int unit = blockIdx.x * kDecWaves + wave;
-  const int tile = unit / nstrips;
-  const int strip = unit - tile * nstrips;
+  const int tile = unit / nspans;
+  const int strip = unit - tile * nspans;
   const int t0 = tile * kDecRows;
   if (it.n_tokens < 1 || t0 >= it.n_tokens) return;
-  const int lam = blockIdx.y >> 1;
-  const bool is_v = blockIdx.y & 1;
+  const int lam = lay_kv >> 1;
+  const bool is_v = lay_kv & 1;
   switch (it.level) {
     case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip); break;
     case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip); break;
@@ -308,9 +329,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
 }
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
-  const int nstrips = (a.c + kStripCh - 1) / kStripCh;
-  const int64_t units = (int64_t)((max_tokens + kDecRows - 1) / kDecRows) * nstrips;
-  dim3 grid((unsigned)((units + kDecWaves - 1) / kDecWaves), (unsigned)(2 * a.l), (unsigned)n_items);
+  const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
+  const int64_t units = (int64_t)((max_tokens + kDecRows - 1) / kDecRows) * nspans;
+  const unsigned gx = (unsigned)((units + kDecWaves - 1) / kDecWaves);
+  dim3 grid = KVH_DEC_SWAP ? dim3(gx, (unsigned)n_items, (unsigned)(2 * a.l)) : dim3(gx, (unsigned)(2 * a.l), (unsigned)n_items);
   if (dt == KVH_F16)
     hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, a);
   else
