@@ -25,6 +25,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
+# HBM bytes per launch on the llama3_8b_8k workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# same command (profiles/codec_kernels_llama3_8b_8k_bf16.md): (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB, the
+# factors being what the counters read for the plain copy kernel of known size.  Re-measure after kernel changes.
+MEASURED_TRAFFIC_BYTES = {
+    ("encode", 8): 1651606528, ("encode", 4): 1367870464, ("encode", 2): 1249452032,
+    ("decode", 8): 1637568512, ("decode", 4): 1369637888, ("decode", 2): 1235354624,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -166,7 +174,8 @@ def main():
         u, b = algorithmic_bytes(l, N, c, bits, n_chunks, chunk)
         per_kernel.append({"kernel": "%s_kernel" % kind, "op": kind, "bits": bits, "avg_ms": avg, "min_ms": min(durs),
                            "uncompressed_GBps": u / avg / 1e6, "algorithmic_bytes": u + b,
-                           "hbm_GBps": (u + b) / avg / 1e6, "hbm_frac": (u + b) / avg / 1e6 / HBM_PEAK_GBPS})
+                           "hbm_GBps": (u + b) / avg / 1e6, "hbm_frac": (u + b) / avg / 1e6 / HBM_PEAK_GBPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((kind, bits)) if args.workload == "llama3_8b_8k" else None})
     dominant = max(per_kernel, key=lambda r: r["avg_ms"])
     dec2 = [r for r in per_kernel if r["op"] == "decode"]
 
@@ -183,7 +192,7 @@ def main():
                    "step": "encode_batch + decode_batch of all %d chunks at each of the 3 levels (6 launches)" % n_chunks},
         "roofline": {"bound": "hbm", "kernel": "%s %d-bit" % (dominant["op"], dominant["bits"]),
                      "achieved": dominant["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": dominant["hbm_frac"], "traffic": None},
+                     "frac": dominant["hbm_frac"], "traffic": dominant["traffic"]},
         "decode_hbm_frac": {str(r["bits"]): r["hbm_frac"] for r in dec2},
         "kernels": per_kernel,
         "copy_probe_GBps": copy_gbps,
