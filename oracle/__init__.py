@@ -72,6 +72,13 @@ def lib() -> ctypes.CDLL:
         L.kvh_ref_t16_to_f32_array.argtypes = [u16p, ctypes.POINTER(ctypes.c_float), ctypes.c_size_t, ctypes.c_int]
         L.kvh_ref_f32_to_t16_array.restype = None
         L.kvh_ref_f32_to_t16_array.argtypes = [ctypes.POINTER(ctypes.c_float), u16p, ctypes.c_size_t, ctypes.c_int]
+        L.kvh_ref_kept_tokens.restype = ctypes.c_int
+        L.kvh_ref_kept_tokens.argtypes = [ctypes.c_int] * 3
+        L.kvh_ref_encode_kept.restype = ctypes.c_int
+        L.kvh_ref_encode_kept.argtypes = [u16p, u16p, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_int] * 7 + [u8p, ctypes.c_size_t]
+        L.kvh_ref_decode_kept.restype = ctypes.c_int
+        L.kvh_ref_decode_kept.argtypes = [u8p, ctypes.c_size_t] + [ctypes.c_int] * 7 + [u16p, u16p, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -207,3 +214,41 @@ def section_offsets(l: int, n: int, c: int, level: int, lam: int):
     if rc != OK:
         raise ValueError("bad arguments: %d" % rc)
     return {"kmeta": out[0], "kcodes": out[1], "vmeta": out[2], "vcodes": out[3], "row_bytes": out[4]}
+
+
+def kept_tokens(N: int, sink: int, window: int) -> int:
+    return lib().kvh_ref_kept_tokens(N, sink, window)
+
+
+def encode_kept(k: np.ndarray, v: np.ndarray, dt: int, sink: int, window: int, level: int) -> np.ndarray:
+    """Token dropping: keep the first `sink` and last `window` tokens of uint16 [l][N][c] K/V, encode them."""
+    l, N, c = k.shape
+    ls, ts = _check_view(k, l, N, c)
+    if _check_view(v, l, N, c) != (ls, ts):
+        raise ValueError("K and V must share strides")
+    n = kept_tokens(N, sink, window)
+    size = blob_size(l, n, c, level) if n > 0 else 0
+    if size == 0:
+        raise ValueError("bad arguments")
+    blob = np.empty(size, dtype=np.uint8)
+    rc = lib().kvh_ref_encode_kept(_u16p(k), _u16p(v), ls, ts, dt, l, N, c, sink, window, level, _u8p(blob), size)
+    if rc != OK:
+        raise RuntimeError("kvh_ref_encode_kept failed: %d" % rc)
+    return blob
+
+
+def decode_kept_into(blob: np.ndarray, dt: int, l: int, N: int, c: int, sink: int, window: int, level: int,
+                     kdst: np.ndarray, vdst: np.ndarray, dst_token0: int = 0, compact: bool = False,
+                     page_table: np.ndarray | None = None, block_tokens: int = 16) -> int:
+    """Decode a token-dropped blob into caller-provided destinations (contiguous or paged); returns the status."""
+    if kdst.dtype != np.uint16 or vdst.dtype != np.uint16 or kdst.strides != vdst.strides:
+        raise ValueError("destinations must be uint16 with equal strides")
+    if page_table is None:
+        ls, ts, pt = kdst.strides[0] // 2, kdst.strides[1] // 2, None
+    else:
+        ls, ts = kdst.strides[0] // 2, kdst.strides[2] // 2
+        page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+        pt = page_table.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    return lib().kvh_ref_decode_kept(_u8p(blob), blob.size, dt, l, N, c, sink, window, level, _u16p(kdst), _u16p(vdst),
+                                     ls, ts, dst_token0, int(compact), pt, block_tokens)

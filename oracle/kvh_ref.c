@@ -25,6 +25,10 @@
  *   pack        codes of one token row in channel order, LSB-first inside each byte
  *   dequantise  q == L and not degenerate: mx;  else T16_rne(fmaf(f32(q), scale, f32(mn)))
  *               (q == 0 therefore gives mn exactly; a degenerate group gives mn everywhere)
+ *   token drop  the second method (keep the beginning and the end of an entry): of N tokens keep the first
+ *               `sink` and the last `window`; the kept tokens, in order, are encoded as an ordinary blob of
+ *               n = min(N, sink + window) tokens whose header also records (N, sink, window); decoding puts
+ *               kept token i back at its original position, or at position i (compact).
  *   blob        64-byte header, then per layer: kmeta | kcodes | vmeta | vcodes, every section
  *               padded to a multiple of 16 bytes.
  */
@@ -140,7 +144,8 @@ static uint16_t get_u16(const uint8_t* p) { return (uint16_t)(p[0] | (p[1] << 8)
 static uint32_t get_u32(const uint8_t* p) { uint32_t v = 0; for (int i = 0; i < 4; ++i) v |= (uint32_t)p[i] << (8 * i); return v; }
 static uint64_t get_u64(const uint8_t* p) { uint64_t v = 0; for (int i = 0; i < 8; ++i) v |= (uint64_t)p[i] << (8 * i); return v; }
 
-static void write_header(uint8_t* blob, int dt, int bits, int l, int n, int c, uint64_t total) {
+static void write_header(uint8_t* blob, int dt, int bits, int l, int n, int c, uint64_t total, uint32_t orig_tokens,
+                         uint32_t sink, uint32_t window) {
   memset(blob, 0, REF_HEADER_BYTES);
   blob[0] = 'K'; blob[1] = 'V'; blob[2] = 'H'; blob[3] = '1';
   put_u16(blob + 4, 1);               /* version */
@@ -152,13 +157,18 @@ static void write_header(uint8_t* blob, int dt, int bits, int l, int n, int c, u
   put_u16(blob + 20, REF_GROUP);      /* K group: tokens   */
   put_u16(blob + 22, REF_GROUP);      /* V group: channels */
   put_u64(blob + 24, total);
+  put_u32(blob + 32, orig_tokens); /* 0: not a token-dropped entry */
+  put_u32(blob + 36, sink);
+  put_u32(blob + 40, window);
 }
 
-static int header_matches(const uint8_t* blob, int dt, int bits, int l, int n, int c, uint64_t total) {
+static int header_matches(const uint8_t* blob, int dt, int bits, int l, int n, int c, uint64_t total, uint32_t orig_tokens,
+                          uint32_t sink, uint32_t window) {
   return blob[0] == 'K' && blob[1] == 'V' && blob[2] == 'H' && blob[3] == '1' && get_u16(blob + 4) == 1 &&
          blob[6] == dt && blob[7] == bits && get_u32(blob + 8) == (uint32_t)l && get_u32(blob + 12) == (uint32_t)n &&
          get_u32(blob + 16) == (uint32_t)c && get_u16(blob + 20) == REF_GROUP && get_u16(blob + 22) == REF_GROUP &&
-         get_u64(blob + 24) == total;
+         get_u64(blob + 24) == total && get_u32(blob + 32) == orig_tokens && get_u32(blob + 36) == sink &&
+         get_u32(blob + 40) == window;
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -235,7 +245,7 @@ int kvh_ref_encode(const uint16_t* k, const uint16_t* v, int64_t layer_stride, i
   int nonfinite = 0;
 
   memset(blob, 0, total); /* padding bytes are zero */
-  write_header(blob, dt, bits, l, n, c, (uint64_t)total);
+  write_header(blob, dt, bits, l, n, c, (uint64_t)total, 0, 0, 0);
   uint8_t* p = blob + REF_HEADER_BYTES;
 
   for (int lam = 0; lam < l; ++lam) {
@@ -308,7 +318,7 @@ int kvh_ref_decode(const uint8_t* blob, size_t blob_len, int dt, int l, int n, i
   if (page_table && block_tokens < 1) return KVH_REF_E_ARG;
   size_t total = kvh_ref_blob_size(l, n, c, level);
   if (blob_len < total) return KVH_REF_E_SIZE;
-  if (!header_matches(blob, dt, bits, l, n, c, (uint64_t)total)) return KVH_REF_E_HEADER;
+  if (!header_matches(blob, dt, bits, l, n, c, (uint64_t)total, 0, 0, 0)) return KVH_REF_E_HEADER;
 
   const size_t row_bytes = (size_t)c * (size_t)bits / 8u;
   const uint8_t* p = blob + REF_HEADER_BYTES;
@@ -356,4 +366,89 @@ void kvh_ref_t16_to_f32_array(const uint16_t* in, float* out, size_t count, int 
 }
 void kvh_ref_f32_to_t16_array(const float* in, uint16_t* out, size_t count, int dt) {
   for (size_t i = 0; i < count; ++i) out[i] = kvh_ref_f32_to_t16(in[i], dt);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Token dropping (the paper's second compression method: Introduction, "some texts are only
+ * important at the beginning and the end"; Preliminary Results, the fixed-rate token-dropping
+ * baseline).  The paper gives no definition; the reading taken: keep the first `sink` and the
+ * last `window` tokens of an entry of N tokens, drop the middle, and store the kept tokens at a
+ * quantised level.  Written as the plain composition gather -> encode and decode -> scatter.
+ * ---------------------------------------------------------------------------------------- */
+#include <stdlib.h>
+
+int kvh_ref_kept_tokens(int N, int sink, int window) {
+  if (N < 1 || sink < 0 || window < 0 || sink + window < 1) return 0;
+  return sink + window >= N ? N : sink + window;
+}
+
+/* original position of kept token i */
+static int64_t kept_position(int i, int N, int sink, int window) {
+  if (sink + window >= N) return i;
+  return i < sink ? i : (int64_t)N - window + (i - sink);
+}
+
+int kvh_ref_encode_kept(const uint16_t* k, const uint16_t* v, int64_t layer_stride, int64_t token_stride, int dt, int l,
+                        int N, int c, int sink, int window, int level, uint8_t* blob, size_t blob_cap) {
+  if (!k || !v || !blob) return KVH_REF_E_ARG;
+  int n = kvh_ref_kept_tokens(N, sink, window);
+  if (n < 1) return KVH_REF_E_SHAPE;
+  if (!shape_ok(l, n, c)) return KVH_REF_E_SHAPE;
+  /* gather the kept rows into a dense [l][n][c] copy, then encode that */
+  uint16_t* gk = (uint16_t*)malloc((size_t)l * n * c * 2);
+  uint16_t* gv = (uint16_t*)malloc((size_t)l * n * c * 2);
+  if (!gk || !gv) { free(gk); free(gv); return KVH_REF_E_SIZE; }
+  for (int lam = 0; lam < l; ++lam)
+    for (int i = 0; i < n; ++i) {
+      int64_t t = kept_position(i, N, sink, window);
+      memcpy(gk + ((size_t)lam * n + i) * c, k + lam * layer_stride + t * token_stride, (size_t)c * 2);
+      memcpy(gv + ((size_t)lam * n + i) * c, v + lam * layer_stride + t * token_stride, (size_t)c * 2);
+    }
+  int rc = kvh_ref_encode(gk, gv, (int64_t)n * c, c, dt, l, n, c, level, blob, blob_cap);
+  free(gk);
+  free(gv);
+  if (rc == KVH_REF_OK || rc == KVH_REF_E_NONFINITE) {
+    put_u32(blob + 32, (uint32_t)N);
+    put_u32(blob + 36, (uint32_t)sink);
+    put_u32(blob + 40, (uint32_t)window);
+  }
+  return rc;
+}
+
+/* compact != 0: kept token i goes to logical position dst_token0 + i; else to dst_token0 + its
+ * original position (rows of dropped tokens are left untouched). */
+int kvh_ref_decode_kept(const uint8_t* blob, size_t blob_len, int dt, int l, int N, int c, int sink, int window, int level,
+                        uint16_t* kdst, uint16_t* vdst, int64_t layer_stride, int64_t token_stride, int64_t dst_token0,
+                        int compact, const int32_t* page_table, int block_tokens) {
+  if (!blob || !kdst || !vdst || dst_token0 < 0) return KVH_REF_E_ARG;
+  int bits = kvh_ref_level_bits(level);
+  if (bits < 0) return KVH_REF_E_LEVEL;
+  int n = kvh_ref_kept_tokens(N, sink, window);
+  if (n < 1 || !shape_ok(l, n, c)) return KVH_REF_E_SHAPE;
+  if (page_table && block_tokens < 1) return KVH_REF_E_ARG;
+  size_t total = kvh_ref_blob_size(l, n, c, level);
+  if (blob_len < total) return KVH_REF_E_SIZE;
+  if (!header_matches(blob, dt, bits, l, n, c, (uint64_t)total, (uint32_t)N, (uint32_t)sink, (uint32_t)window))
+    return KVH_REF_E_HEADER;
+  /* decode into a dense temporary with the ordinary decoder (on a copy whose drop words are cleared), then scatter */
+  uint8_t* plain = (uint8_t*)malloc(total);
+  uint16_t* dk = (uint16_t*)malloc((size_t)l * n * c * 2);
+  uint16_t* dv = (uint16_t*)malloc((size_t)l * n * c * 2);
+  if (!plain || !dk || !dv) { free(plain); free(dk); free(dv); return KVH_REF_E_SIZE; }
+  memcpy(plain, blob, total);
+  memset(plain + 32, 0, 12);
+  int rc = kvh_ref_decode(plain, total, dt, l, n, c, level, dk, dv, (int64_t)n * c, c, 0, NULL, 0);
+  if (rc == KVH_REF_OK) {
+    for (int lam = 0; lam < l; ++lam)
+      for (int i = 0; i < n; ++i) {
+        int64_t s = dst_token0 + (compact ? i : kept_position(i, N, sink, window));
+        int64_t row = page_table ? (int64_t)page_table[s / block_tokens] * block_tokens + s % block_tokens : s;
+        memcpy(kdst + lam * layer_stride + row * token_stride, dk + ((size_t)lam * n + i) * c, (size_t)c * 2);
+        memcpy(vdst + lam * layer_stride + row * token_stride, dv + ((size_t)lam * n + i) * c, (size_t)c * 2);
+      }
+  }
+  free(plain);
+  free(dk);
+  free(dv);
+  return rc;
 }
