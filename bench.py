@@ -161,6 +161,32 @@ def main():
         pe[1].record(stream)
         torch.cuda.synchronize()
     copy_gbps = 5 * 2 * (1 << 30) / pe[0].elapsed_time(pe[1]) / 1e6
+
+    # Also outside the timed region: the token-dropping method on the whole tensor as ONE entry of N tokens,
+    # keeping sink = 128 and window = N/2 - 128 tokens (rate 1/2), stored at 8 and at 2 bits.
+    dropping = []
+    with torch.cuda.stream(stream):
+        sink, window = 128, N // 2 - 128
+        n_kept = kvh.kept_tokens(N, sink, window)
+        st1 = torch.zeros(1, dtype=torch.int32, device=dev)
+        for level in (0, 2):
+            kblob = torch.empty(kvh.blob_size(l, n_kept, c, level), dtype=torch.uint8, device=dev)
+            fns = {"encode_kept": lambda: kvh.encode_kept(kv[0], kv[1], sink, window, level, blob=kblob, stream=stream),
+                   "decode_kept": lambda: kvh.decode_kept(kblob, level, N, sink, window, out[0], out[1], status=st1, stream=stream)}
+            for name, fn in fns.items():
+                fn()
+                de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                de[0].record(stream)
+                for _ in range(5):
+                    fn()
+                de[1].record(stream)
+                torch.cuda.synchronize()
+                ms = de[0].elapsed_time(de[1]) / 5
+                kept_bytes = 2 * l * n_kept * c * 2
+                dropping.append({"op": name, "bits": kvh.level_bits(level), "kept_tokens": n_kept, "of": N, "avg_ms": ms,
+                                 "kept_uncompressed_GBps": kept_bytes / ms / 1e6,
+                                 "hbm_frac": (kept_bytes + kblob.numel()) / ms / 1e6 / HBM_PEAK_GBPS})
+        assert int(st1.item()) == 0
     step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
@@ -196,6 +222,7 @@ def main():
         "decode_hbm_frac": {str(r["bits"]): r["hbm_frac"] for r in dec2},
         "kernels": per_kernel,
         "copy_probe_GBps": copy_gbps,
+        "token_dropping": dropping,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),
     }

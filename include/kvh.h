@@ -19,7 +19,8 @@
  *
  * Blob (little-endian, position independent, movable with memcpy between storage tiers):
  *   64-byte header { u32 magic 'KVH1'; u16 version = 1; u8 dtype; u8 bits; u32 l; u32 n; u32 c;
- *                    u16 k_group = 128; u16 v_group = 128; u64 total_bytes; zero padding }
+ *                    u16 k_group = 128; u16 v_group = 128; u64 total_bytes;
+ *                    u32 orig_tokens; u32 sink; u32 window (token dropping; 0 otherwise); zero padding }
  *   then for each layer:  kmeta[ceil(n/128)][c]{mn,mx}  kcodes[n][c*b/8]
  *                         vmeta[n][c/128]{mn,mx}        vcodes[n][c*b/8]
  *   each section padded with zero bytes to a multiple of 16.
@@ -140,6 +141,32 @@ typedef struct {
  * Destinations of different items must not overlap.  n_items <= 65535. */
 int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
                      const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
+
+/* ---- Token dropping ------------------------------------------------------------------------------
+ * The paper's second compression method: some contexts "are only important at the beginning and the
+ * end (which is suitable for token dropping)" (Introduction); the evaluation's fixed-rate
+ * token-dropping baseline (Preliminary Results).  The paper defines nothing further; here an entry of N
+ * tokens keeps its first `sink` and last `window` tokens (all of them if sink + window >= N) and the
+ * kept tokens, in order, are stored as an ordinary blob of n = kvh_kept_tokens(N, sink, window) tokens
+ * at a quantised level, so dropping composes with quantisation.  Header bytes 32..43 record
+ * (N, sink, window); they are zero in ordinary blobs, and kvh_decode / kvh_decode_batch reject a blob
+ * in which they are not. */
+
+/* Number of tokens kept: min(N, sink + window); 0 on bad arguments (N < 1, negative, sink + window < 1). */
+int kvh_kept_tokens(int N, int sink, int window);
+
+/* Gather the kept tokens of `kv` (a view of N tokens) and encode them into one blob at `level`.
+ * blob_cap must be >= kvh_blob_size(l, kvh_kept_tokens(N, sink, window), c, level). */
+int kvh_encode_kept(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int sink, int window, int level,
+                    void* blob_dev, size_t blob_cap, void* stream);
+
+/* Decode a token-dropped blob.  compact == 0: kept token i goes back to logical position dst_token0 +
+ * (its original position), the rows of dropped tokens are not touched; compact != 0: to dst_token0 + i.
+ * Contiguous or paged destination and status word as for kvh_decode; (N, sink, window) must equal the
+ * values the blob was encoded with, else KVH_DEV_HEADER_MISMATCH and nothing is written. */
+int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int sink, int window, int level,
+                    const kvh_kv_view* dst, int64_t dst_token0, int compact, const int32_t* page_table_dev,
+                    int block_tokens, int32_t* status_dev, void* stream);
 
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
  * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that

@@ -6,6 +6,6 @@ marshals arguments.  torch is used for device memory and streams.  There is no C
 importing the binding without a built library raises.
 """
 from .binding import (  # noqa: F401
-    BF16, F16, KVHError, blob_size, copy_probe, decode, decode_batch, encode, encode_batch, encode_chunked,
-    level_bits, lib, make_dec_items, make_enc_items, num_levels, strerror,
+    BF16, F16, KVHError, blob_size, copy_probe, decode, decode_batch, decode_kept, encode, encode_batch,
+    encode_chunked, encode_kept, kept_tokens, level_bits, lib, make_dec_items, make_enc_items, num_levels, strerror,
 )

@@ -61,6 +61,12 @@ def lib() -> ctypes.CDLL:
         L.kvh_decode.argtypes = [vp, i32, i32, i32, i32, i32, view, i64, vp, i32, vp, vp]
         L.kvh_decode_batch.restype = i32
         L.kvh_decode_batch.argtypes = [vp, i32, i32, i32, i32, i32, view, i32, vp, vp]
+        L.kvh_kept_tokens.restype = i32
+        L.kvh_kept_tokens.argtypes = [i32, i32, i32]
+        L.kvh_encode_kept.restype = i32
+        L.kvh_encode_kept.argtypes = [view, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.kvh_decode_kept.restype = i32
+        L.kvh_decode_kept.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, view, i64, i32, vp, i32, vp, vp]
         L.kvh_copy_probe.restype = i32
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_strerror.restype = ctypes.c_char_p
@@ -205,6 +211,44 @@ def decode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, k_
     _check(lib().kvh_decode_batch(items.data_ptr(), n_items, max_tokens_per_item, dt, l, c, ctypes.byref(view),
                                   block_tokens, status.data_ptr() if status is not None else None,
                                   _stream_ptr(stream)), "kvh_decode_batch")
+
+
+def kept_tokens(N: int, sink: int, window: int) -> int:
+    return lib().kvh_kept_tokens(N, sink, window)
+
+
+def encode_kept(k: torch.Tensor, v: torch.Tensor, sink: int, window: int, level: int,
+                blob: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """kvh_encode_kept: keep the first `sink` and last `window` tokens of K/V [l][N][c], encode them."""
+    view, dt = _view(k, v)
+    l, N, c = k.shape
+    if blob is None:
+        size = blob_size(l, kept_tokens(N, sink, window), c, level)
+        if size == 0:
+            _check(lib().kvh_encode_kept(ctypes.byref(view), dt, l, N, c, sink, window, level, None, 0, None), "kvh_encode_kept")
+        blob = torch.empty(size, dtype=torch.uint8, device=k.device)
+    _require_cuda(blob)
+    _check(lib().kvh_encode_kept(ctypes.byref(view), dt, l, N, c, sink, window, level, blob.data_ptr(), blob.numel(),
+                                 _stream_ptr(stream)), "kvh_encode_kept")
+    return blob
+
+
+def decode_kept(blob: torch.Tensor, level: int, N: int, sink: int, window: int, k_dst: torch.Tensor, v_dst: torch.Tensor,
+                dst_token0: int = 0, compact: bool = False, page_table: torch.Tensor | None = None, block_tokens: int = 16,
+                status: torch.Tensor | None = None, stream=None) -> None:
+    """kvh_decode_kept: a token-dropped blob -> original (or compact) rows of a contiguous or paged destination."""
+    paged = page_table is not None
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(blob, page_table, status)
+    if paged and page_table.dtype != torch.int32:
+        raise ValueError("page_table must be int32")
+    if status is not None and status.dtype != torch.int32:
+        raise ValueError("status must be int32")
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_decode_kept(blob.data_ptr(), dt, l, N, c, sink, window, level, ctypes.byref(view), dst_token0,
+                                 int(compact), page_table.data_ptr() if paged else None, block_tokens,
+                                 status.data_ptr() if status is not None else None, _stream_ptr(stream)),
+           "kvh_decode_kept")
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

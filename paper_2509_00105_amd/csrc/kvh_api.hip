@@ -69,6 +69,7 @@ int kvh_encode(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int lev
   a.token_stride = kv->token_stride;
   a.l = l;
   a.c = c;
+  a.split = kNoSplit;
   return launch_encode(a, dt, 1, N, static_cast<hipStream_t>(stream));
 }
 
@@ -97,6 +98,7 @@ int kvh_encode_chunked(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c,
   a.token_stride = kv->token_stride;
   a.l = l;
   a.c = c;
+  a.split = kNoSplit;
   for (int i = 0; i < n_chunks; ++i) {
     const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
     a.one = kvh_enc_item{static_cast<uint8_t*>(blobs_dev) + blob_offsets[i], (int64_t)i * chunk, n, levels[i]};
@@ -118,6 +120,7 @@ int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_
   a.token_stride = src->token_stride;
   a.l = l;
   a.c = c;
+  a.split = kNoSplit;
   return launch_encode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
 }
 
@@ -141,6 +144,7 @@ int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, i
   a.l = l;
   a.c = c;
   a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
+  a.split = kNoSplit;
   return launch_decode(a, dt, 1, n_tokens, static_cast<hipStream_t>(stream));
 }
 
@@ -161,7 +165,73 @@ int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_
   a.l = l;
   a.c = c;
   a.block_tokens = block_tokens;
+  a.split = kNoSplit;
   return launch_decode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
+int kvh_kept_tokens(int N, int sink, int window) {
+  if (N < 1 || sink < 0 || window < 0 || (int64_t)sink + window < 1) return 0;
+  return (int64_t)sink + window >= N ? N : sink + window;
+}
+
+int kvh_encode_kept(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int sink, int window, int level,
+                    void* blob_dev, size_t blob_cap, void* stream) {
+  if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (int rc = check_view(kv)) return rc;
+  if (level_bits(level) < 0) return KVH_E_LEVEL;
+  const int n = kvh_kept_tokens(N, sink, window);
+  if (n < 1) return KVH_E_SHAPE;
+  if (int rc = check_shape(l, n, c)) return rc;
+  if (blob_cap < kvh_blob_size(l, n, c, level)) return KVH_E_SIZE;
+  if (!aligned16(blob_dev)) return KVH_E_ALIGN;
+  EncodeParams a{};
+  a.items = nullptr;
+  a.one = kvh_enc_item{blob_dev, 0, n, level};
+  a.k = static_cast<const uint16_t*>(kv->k);
+  a.v = static_cast<const uint16_t*>(kv->v);
+  a.layer_stride = kv->layer_stride;
+  a.token_stride = kv->token_stride;
+  a.l = l;
+  a.c = c;
+  const bool drops = n < N;
+  a.split = drops ? sink : kNoSplit;  // kept token t >= sink is source token t + (N - window - sink)
+  a.jump = drops ? (int64_t)N - window - sink : 0;
+  a.hdr_orig_tokens = (uint32_t)N;
+  a.hdr_sink = (uint32_t)sink;
+  a.hdr_window = (uint32_t)window;
+  return launch_encode(a, dt, 1, n, static_cast<hipStream_t>(stream));
+}
+
+int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int sink, int window, int level,
+                    const kvh_kv_view* dst, int64_t dst_token0, int compact, const int32_t* page_table_dev,
+                    int block_tokens, int32_t* status_dev, void* stream) {
+  if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16) || dst_token0 < 0) return KVH_E_ARG;
+  if (int rc = check_view(dst)) return rc;
+  if (level_bits(level) < 0) return KVH_E_LEVEL;
+  const int n = kvh_kept_tokens(N, sink, window);
+  if (n < 1) return KVH_E_SHAPE;
+  if (int rc = check_shape(l, n, c)) return rc;
+  if (page_table_dev != nullptr && block_tokens < 1) return KVH_E_ARG;
+  if (dst_token0 + N > INT32_MAX) return KVH_E_ARG;
+  if (!aligned16(blob_dev)) return KVH_E_ALIGN;
+  DecodeParams a{};
+  a.items = nullptr;
+  a.one = kvh_item{blob_dev, n, level, dst_token0, page_table_dev};
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
+  const bool hops = n < N && !compact;
+  a.split = hops ? sink : kNoSplit;
+  a.jump = hops ? (int64_t)N - window - sink : 0;
+  a.hdr_orig_tokens = (uint32_t)N;
+  a.hdr_sink = (uint32_t)sink;
+  a.hdr_window = (uint32_t)window;
+  return launch_decode(a, dt, 1, n, static_cast<hipStream_t>(stream));
 }
 
 int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {

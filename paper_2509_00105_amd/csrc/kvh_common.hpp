@@ -94,6 +94,11 @@ struct DecodeParams {
   int64_t layer_stride, token_stride;  // elements
   int32_t* status;                     // nullable; indexed by item
   int l, c, block_tokens;
+  // Token-dropped entries (single-item calls only): token t >= split lands `jump` rows further on,
+  // and the header must carry these three words (all zero for an ordinary blob).
+  int32_t split;
+  int64_t jump;
+  uint32_t hdr_orig_tokens, hdr_sink, hdr_window;
 };
 
 struct EncodeParams {
@@ -103,7 +108,14 @@ struct EncodeParams {
   const uint16_t* v;
   int64_t layer_stride, token_stride;  // elements
   int l, c;
+  // Token-dropped entries (single-item calls only): token t >= split is read `jump` rows further on,
+  // and the header records these three words (all zero for an ordinary blob).
+  int32_t split;
+  int64_t jump;
+  uint32_t hdr_orig_tokens, hdr_sink, hdr_window;
 };
+
+constexpr int32_t kNoSplit = 0x7fffffff;
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
 int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);

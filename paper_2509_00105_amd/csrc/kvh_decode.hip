@@ -151,16 +151,17 @@ __device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_t
 }
 
 struct HeaderWords {
-  uintx4 a, b;
+  uintx4 a, b, c;
 };
 __device__ __forceinline__ HeaderWords load_header(const uint8_t* blob) {
-  return {gload<uintx4>(blob), gload<uintx4>(blob + 16)};
+  return {gload<uintx4>(blob), gload<uintx4>(blob + 16), gload<uintx4>(blob + 32)};
 }
 __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int bits, int l, int n, int c,
-                                               size_t total) {
+                                               size_t total, uint32_t orig_tokens, uint32_t sink, uint32_t window) {
   return h.a.x == kMagic && h.a.y == (1u | (uint32_t)dt << 16 | (uint32_t)bits << 24) && h.a.z == (uint32_t)l &&
          h.a.w == (uint32_t)n && h.b.x == (uint32_t)c && h.b.y == ((uint32_t)kGroup | (uint32_t)kGroup << 16) &&
-         h.b.z == (uint32_t)total && h.b.w == (uint32_t)((uint64_t)total >> 32);
+         h.b.z == (uint32_t)total && h.b.w == (uint32_t)((uint64_t)total >> 32) && h.c.x == orig_tokens &&
+         h.c.y == sink && h.c.z == window;
 }
 
 // One unit: every load the unit needs (header, page-table entries, metadata, codes) is issued
@@ -192,7 +193,9 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   int32_t my_row = 0;
   {
     int t = t0 + (lane & (kDecRows - 1));
-    if (t < n) my_row = physical_row(it.dst_token0 + t, it.page_table, a.block_tokens);
+    const bool batch = a.items != nullptr;  // batch items are never token-dropped entries
+    const int64_t hop = (!batch && t >= a.split) ? a.jump : 0;
+    if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
   }
 
   const uint8_t* kmeta = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
@@ -229,7 +232,9 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     for (int s = 0; s < kDecSegs; ++s) cw[i][s].load(codes + (size_t)t * geo.row_bytes + ch[s] * BITS / 8);
   }
 
-  if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes())) {
+  const bool plain = a.items != nullptr;
+  if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes(),
+                      plain ? 0u : a.hdr_orig_tokens, plain ? 0u : a.hdr_sink, plain ? 0u : a.hdr_window)) {
     if (a.status != nullptr && lane == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
     return;
   }

@@ -103,7 +103,8 @@ __device__ __forceinline__ void quantise_store8(uint8_t* p, const float (&x)[8],
 
 template <int DT, int BITS>
 __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_enc_item& it, uint8_t* layer_base,
-                                               const LayerGeom& geo, int lam, int g, int strip, float* red) {
+                                               const LayerGeom& geo, int lam, int g, int strip, float* red,
+                                               int split, int64_t jump) {
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = it.n_tokens;
@@ -121,7 +122,7 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
   for (int i = 0; i < kEncRows; ++i) {
     int t = t_first + i;
     t = t < n ? t : n - 1;
-    d[i] = gload<uintx4>(src + (it.src_token0 + t) * a.token_stride * 2 + lane_src_off);
+    d[i] = gload<uintx4>(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2 + lane_src_off);
   }
   float mn[8], mx[8];
   unpack8<DT>(d[0], mn);
@@ -228,7 +229,8 @@ __device__ __forceinline__ float row16_reduce(float v) {
 
 template <int DT, int BITS>
 __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_enc_item& it, uint8_t* layer_base,
-                                               const LayerGeom& geo, int lam, int tile, int strip) {
+                                               const LayerGeom& geo, int lam, int tile, int strip, int split,
+                                               int64_t jump) {
   constexpr int kBatch = 8;  // rows in flight per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -252,7 +254,7 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
     for (int i = 0; i < kBatch; ++i) {
       int t = t_first + i0 + i;
       t = t < n ? t : n - 1;
-      d[i] = gload<uintx4>(src + (it.src_token0 + t) * a.token_stride * 2 + lane_src_off);
+      d[i] = gload<uintx4>(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2 + lane_src_off);
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
@@ -302,6 +304,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   } else {
     it = a.one;
   }
+  const int split = a.items != nullptr ? kNoSplit : a.split;  // batch items are never token-dropped entries
+  const int64_t jump = a.items != nullptr ? 0 : a.jump;
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
   const int tile = blockIdx.x / nstrips;
   const int strip = blockIdx.x - tile * nstrips;
@@ -324,6 +328,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
       case 5: w = (uint32_t)kGroup | (uint32_t)kGroup << 16; break;
       case 6: w = (uint32_t)total; break;
       case 7: w = (uint32_t)(total >> 32); break;
+      case 8: w = a.items != nullptr ? 0u : a.hdr_orig_tokens; break;
+      case 9: w = a.items != nullptr ? 0u : a.hdr_sink; break;
+      case 10: w = a.items != nullptr ? 0u : a.hdr_window; break;
       default: break;
     }
     gstore<uint32_t>(blob + 4 * threadIdx.x, w);
@@ -331,15 +338,15 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   uint8_t* layer_base = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
   if (!is_v) {
     switch (bits) {
-      case 8: encode_k_block<DT, 8>(a, it, layer_base, geo, lam, tile, strip, red); break;
-      case 4: encode_k_block<DT, 4>(a, it, layer_base, geo, lam, tile, strip, red); break;
-      default: encode_k_block<DT, 2>(a, it, layer_base, geo, lam, tile, strip, red); break;
+      case 8: encode_k_block<DT, 8>(a, it, layer_base, geo, lam, tile, strip, red, split, jump); break;
+      case 4: encode_k_block<DT, 4>(a, it, layer_base, geo, lam, tile, strip, red, split, jump); break;
+      default: encode_k_block<DT, 2>(a, it, layer_base, geo, lam, tile, strip, red, split, jump); break;
     }
   } else {
     switch (bits) {
-      case 8: encode_v_block<DT, 8>(a, it, layer_base, geo, lam, tile, strip); break;
-      case 4: encode_v_block<DT, 4>(a, it, layer_base, geo, lam, tile, strip); break;
-      default: encode_v_block<DT, 2>(a, it, layer_base, geo, lam, tile, strip); break;
+      case 8: encode_v_block<DT, 8>(a, it, layer_base, geo, lam, tile, strip, split, jump); break;
+      case 4: encode_v_block<DT, 4>(a, it, layer_base, geo, lam, tile, strip, split, jump); break;
+      default: encode_v_block<DT, 2>(a, it, layer_base, geo, lam, tile, strip, split, jump); break;
     }
   }
 }

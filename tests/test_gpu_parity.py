@@ -260,3 +260,64 @@ def test_idempotent_reencoding_on_gpu(kvh):
             again = kvh.encode(ok, ov, level)
             torch.cuda.synchronize()
             assert torch.equal(blob, again)
+
+
+# ---------------------------------------------------------------------------------------------
+# token dropping (keep the first `sink` and the last `window` tokens, encode them at a level)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("N,sink,window", [(300, 4, 124), (515, 128, 200), (130, 1, 1), (64, 100, 100), (700, 0, 257),
+                                           (1000, 130, 0)])
+def test_token_dropping_matches_oracle(kvh, N, sink, window, dt):
+    l, c = 2, 640
+    k, v = gen.make_kv(l, N, c, dt, seed=N + sink + window)
+    kd, vd = to_dev(k, dt), to_dev(v, dt)
+    n = oracle.kept_tokens(N, sink, window)
+    assert kvh.kept_tokens(N, sink, window) == n
+    for level in range(3):
+        want = oracle.encode_kept(k, v, dt, sink, window, level)
+        blob = kvh.encode_kept(kd, vd, sink, window, level)
+        torch.cuda.synchronize()
+        assert_same_blob(blob.cpu().numpy(), want, "encode_kept N=%d sink=%d window=%d level %d" % (N, sink, window, level))
+        for compact in (False, True):
+            wk = np.full((l, N + 40, c), 0x5A5A, dtype=np.uint16); wv = wk.copy()
+            assert oracle.decode_kept_into(want, dt, l, N, c, sink, window, level, wk, wv, 24, compact) == 0
+            gk, gv = to_dev(np.full_like(wk, 0x5A5A), dt), to_dev(np.full_like(wk, 0x5A5A), dt)
+            status = torch.zeros(1, dtype=torch.int32, device="cuda")
+            kvh.decode_kept(torch.from_numpy(want).cuda(), level, N, sink, window, gk, gv, dst_token0=24, compact=compact,
+                            status=status)
+            torch.cuda.synchronize()
+            assert status.item() == 0
+            assert_same_bits(to_host(gk), wk, dt, "decode_kept K compact=%s" % compact)
+            assert_same_bits(to_host(gv), wv, dt, "decode_kept V compact=%s" % compact)
+
+
+def test_token_dropping_paged_and_header_checks(kvh):
+    dt, l, N, c, sink, window, level, bt, pool, t0 = BF16, 2, 400, 256, 20, 150, 2, 16, 40, 32
+    k, v = gen.make_kv(l, N, c, dt, seed=77)
+    want = oracle.encode_kept(k, v, dt, sink, window, level)
+    blob = torch.from_numpy(want).cuda()
+    table = np.random.default_rng(5).permutation(pool).astype(np.int32)[: -(-(t0 + N) // bt)]
+    wk = np.full((l, pool, bt, c), 0x1111, dtype=np.uint16); wv = wk.copy()
+    assert oracle.decode_kept_into(want, dt, l, N, c, sink, window, level, wk, wv, t0, False, table, bt) == 0
+    gk, gv = to_dev(np.full_like(wk, 0x1111), dt), to_dev(np.full_like(wk, 0x1111), dt)
+    kvh.decode_kept(blob, level, N, sink, window, gk, gv, dst_token0=t0, page_table=torch.from_numpy(table).cuda(),
+                    block_tokens=bt)
+    torch.cuda.synchronize()
+    assert_same_bits(to_host(gk), wk, dt, "paged K"); assert_same_bits(to_host(gv), wv, dt, "paged V")
+    # a dropped blob is not an ordinary blob, and the split must match
+    n = kvh.kept_tokens(N, sink, window)
+    ok = torch.full((l, N, c), 3.0, dtype=torch.bfloat16, device="cuda"); ov = ok.clone()
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kvh.decode(blob, level, n, ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 1 and bool((ok == 3.0).all())
+    status.zero_()
+    kvh.decode_kept(blob, level, N, window, sink, ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 1 and bool((ok == 3.0).all()) and bool((ov == 3.0).all())
+    plain = torch.from_numpy(oracle.encode(k[:, :n], v[:, :n], dt, level)).cuda()
+    status.zero_()
+    kvh.decode_kept(plain, level, N, sink, window, ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 1 and bool((ok == 3.0).all())
