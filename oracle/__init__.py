@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         L.kvh_ref_decode_kept.restype = ctypes.c_int
         L.kvh_ref_decode_kept.argtypes = [u8p, ctypes.c_size_t] + [ctypes.c_int] * 7 + [u16p, u16p, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.c_int, i32p, ctypes.c_int]
+        L.kvh_ref_transcode.restype = ctypes.c_int
+        L.kvh_ref_transcode.argtypes = [u8p, ctypes.c_size_t] + [ctypes.c_int] * 6 + [u8p, ctypes.c_size_t]
         _lib = L
     return _lib
 
@@ -252,3 +254,21 @@ def decode_kept_into(blob: np.ndarray, dt: int, l: int, N: int, c: int, sink: in
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
     return lib().kvh_ref_decode_kept(_u8p(blob), blob.size, dt, l, N, c, sink, window, level, _u16p(kdst), _u16p(vdst),
                                      ls, ts, dst_token0, int(compact), pt, block_tokens)
+
+
+def transcode_rc(blob: np.ndarray, dt: int, l: int, n: int, c: int, level_in: int, level_out: int, out: np.ndarray) -> int:
+    """Raw status-returning form of transcode."""
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    return lib().kvh_ref_transcode(_u8p(blob), blob.size, dt, l, n, c, level_in, level_out, _u8p(out), out.size)
+
+
+def transcode(blob: np.ndarray, dt: int, l: int, n: int, c: int, level_in: int, level_out: int) -> np.ndarray:
+    """Re-compress a blob of n stored tokens from level_in to level_out: decode, then encode."""
+    size = blob_size(l, n, c, level_out)
+    if size == 0:
+        raise ValueError("bad level or shape")
+    out = np.empty(size, dtype=np.uint8)
+    rc = transcode_rc(blob, dt, l, n, c, level_in, level_out, out)
+    if rc != OK:
+        raise RuntimeError("kvh_ref_transcode failed: %d" % rc)
+    return out

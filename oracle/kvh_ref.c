@@ -452,3 +452,43 @@ int kvh_ref_decode_kept(const uint8_t* blob, size_t blob_len, int dt, int l, int
   free(dv);
   return rc;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Transcode: re-compress a stored entry from the level it is held at to another level (the
+ * greedy step of the policy compresses an entry further, from rate m to rate n; Design section,
+ * marginal utility drop).  Defined as nothing more than decode followed by encode; the
+ * token-dropping words of the header are carried over unchanged.
+ * ---------------------------------------------------------------------------------------- */
+int kvh_ref_transcode(const uint8_t* blob_in, size_t len_in, int dt, int l, int n, int c, int level_in, int level_out,
+                      uint8_t* blob_out, size_t cap_out) {
+  if (!blob_in || !blob_out) return KVH_REF_E_ARG;
+  int bits_in = kvh_ref_level_bits(level_in);
+  if (bits_in < 0 || kvh_ref_level_bits(level_out) < 0) return KVH_REF_E_LEVEL;
+  if (!shape_ok(l, n, c)) return KVH_REF_E_SHAPE;
+  size_t total_in = kvh_ref_blob_size(l, n, c, level_in);
+  size_t total_out = kvh_ref_blob_size(l, n, c, level_out);
+  if (len_in < total_in || cap_out < total_out) return KVH_REF_E_SIZE;
+  uint32_t orig = get_u32(blob_in + 32), sink = get_u32(blob_in + 36), window = get_u32(blob_in + 40);
+  if (!header_matches(blob_in, dt, bits_in, l, n, c, (uint64_t)total_in, orig, sink, window)) return KVH_REF_E_HEADER;
+  if ((orig | sink | window) != 0 &&
+      (orig > 0x7fffffffu || sink > 0x7fffffffu || window > 0x7fffffffu || (uint64_t)sink + window > 0x7fffffffu ||
+       kvh_ref_kept_tokens((int)orig, (int)sink, (int)window) != n))
+    return KVH_REF_E_HEADER;
+  uint8_t* plain = (uint8_t*)malloc(total_in);
+  uint16_t* dk = (uint16_t*)malloc((size_t)l * n * c * 2);
+  uint16_t* dv = (uint16_t*)malloc((size_t)l * n * c * 2);
+  if (!plain || !dk || !dv) { free(plain); free(dk); free(dv); return KVH_REF_E_SIZE; }
+  memcpy(plain, blob_in, total_in);
+  memset(plain + 32, 0, 12);
+  int rc = kvh_ref_decode(plain, total_in, dt, l, n, c, level_in, dk, dv, (int64_t)n * c, c, 0, NULL, 0);
+  if (rc == KVH_REF_OK) rc = kvh_ref_encode(dk, dv, (int64_t)n * c, c, dt, l, n, c, level_out, blob_out, cap_out);
+  if (rc == KVH_REF_OK) {
+    put_u32(blob_out + 32, orig);
+    put_u32(blob_out + 36, sink);
+    put_u32(blob_out + 40, window);
+  }
+  free(plain);
+  free(dk);
+  free(dv);
+  return rc;
+}
