@@ -168,6 +168,40 @@ int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int
                     const kvh_kv_view* dst, int64_t dst_token0, int compact, const int32_t* page_table_dev,
                     int block_tokens, int32_t* status_dev, void* stream);
 
+/* ---- Transcode ------------------------------------------------------------------------------------
+ * The paper's policy lowers the quality of stored entries step by step ("compress furthermore" from
+ * rate m to rate n; Design section, marginal utility drop).  kvh_transcode re-compresses a stored blob
+ * from level_in to level_out in one kernel, without materialising 16-bit KV: the output is, byte for
+ * byte, what kvh_encode would produce from the tensors kvh_decode writes for the source blob.
+ * Precondition: the source blob was written by this library (encode, encode_kept or transcode), so that
+ * every group holds its smallest and largest code; a hand-made blob without that property gets the
+ * source's group statistics instead of recomputed ones.  Token-dropping header words are carried over.
+ * Source and destination must not overlap.  Any pair of levels is allowed (going up only re-packs what
+ * the lower level kept). */
+
+/* The kernel checks the source header against (dt, l, n_tokens, c, level_in) — n_tokens is the number
+ * of tokens stored in the blob — and on disagreement writes KVH_DEV_HEADER_MISMATCH to *status_dev (if
+ * not NULL; zeroed by the caller) and nothing else.  dst_cap must be >= kvh_blob_size(l, n_tokens, c,
+ * level_out); the caller guarantees kvh_blob_size(l, n_tokens, c, level_in) readable bytes at src_dev. */
+int kvh_transcode(const void* src_dev, kvh_dtype dt, int l, int n_tokens, int c, int level_in, int level_out,
+                  void* dst_dev, size_t dst_cap, int32_t* status_dev, void* stream);
+
+/* One transcode job of a batch.  The ARRAY of items lives in device memory. */
+typedef struct {
+  const void* src;   /* device pointer, 16-byte aligned: blob stored at level_in */
+  void* dst;         /* device pointer, 16-byte aligned: room for kvh_blob_size(l, n_tokens, c, level_out) */
+  int32_t n_tokens;  /* tokens stored in the blob, 1 .. max_tokens_per_item */
+  int32_t level_in;  /* 0 .. 2 */
+  int32_t level_out; /* 0 .. 2 */
+  int32_t reserved;  /* 0 */
+} kvh_tc_item;
+
+/* Transcode many blobs (mixed lengths and level pairs) in ONE launch.  status_dev as for
+ * kvh_decode_batch; items with n_tokens < 1 are skipped, items with a level out of range get
+ * KVH_DEV_HEADER_MISMATCH.  Buffers of different items must not overlap.  n_items <= 65535. */
+int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                        int32_t* status_dev, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
  * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that
  * scales the HBM byte counters and as the practical copy-bandwidth ceiling of the device. */

@@ -7,5 +7,6 @@ importing the binding without a built library raises.
 """
 from .binding import (  # noqa: F401
     BF16, F16, KVHError, blob_size, copy_probe, decode, decode_batch, decode_kept, encode, encode_batch,
-    encode_chunked, encode_kept, kept_tokens, level_bits, lib, make_dec_items, make_enc_items, num_levels, strerror,
+    encode_chunked, encode_kept, kept_tokens, level_bits, lib, make_dec_items, make_enc_items, make_tc_items, num_levels,
+    strerror, transcode, transcode_batch,
 )

@@ -29,7 +29,9 @@ class _KVView(ctypes.Structure):
 ENC_ITEM = np.dtype([("blob", "<u8"), ("src_token0", "<i8"), ("n_tokens", "<i4"), ("level", "<i4")], align=True)
 DEC_ITEM = np.dtype([("blob", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"),
                      ("page_table", "<u8")], align=True)
-assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32
+TC_ITEM = np.dtype([("src", "<u8"), ("dst", "<u8"), ("n_tokens", "<i4"), ("level_in", "<i4"), ("level_out", "<i4"),
+                    ("reserved", "<i4")], align=True)
+assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32
 
 _lib = None
 
@@ -67,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.kvh_encode_kept.argtypes = [view, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         L.kvh_decode_kept.restype = i32
         L.kvh_decode_kept.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, view, i64, i32, vp, i32, vp, vp]
+        L.kvh_transcode.restype = i32
+        L.kvh_transcode.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp]
+        L.kvh_transcode_batch.restype = i32
+        L.kvh_transcode_batch.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.kvh_copy_probe.restype = i32
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_strerror.restype = ctypes.c_char_p
@@ -249,6 +255,50 @@ def decode_kept(blob: torch.Tensor, level: int, N: int, sink: int, window: int, 
                                  int(compact), page_table.data_ptr() if paged else None, block_tokens,
                                  status.data_ptr() if status is not None else None, _stream_ptr(stream)),
            "kvh_decode_kept")
+
+
+def _dt_code(dtype) -> int:
+    if dtype in _TORCH_DT:
+        return _TORCH_DT[dtype]
+    if dtype in (F16, BF16):
+        return int(dtype)
+    raise ValueError("dtype must be torch.float16, torch.bfloat16, F16 or BF16")
+
+
+def transcode(blob: torch.Tensor, dtype, l: int, n_tokens: int, c: int, level_in: int, level_out: int,
+              out: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """kvh_transcode: a blob of n_tokens stored tokens at level_in -> a blob at level_out (uint8 device tensor)."""
+    _require_cuda(blob, out, status)
+    dt = _dt_code(dtype)
+    if status is not None and status.dtype != torch.int32:
+        raise ValueError("status must be int32")
+    if out is None:
+        size = blob_size(l, n_tokens, c, level_out)
+        if size == 0:
+            _check(lib().kvh_transcode(blob.data_ptr(), dt, l, n_tokens, c, level_in, level_out, None, 0, None, None),
+                   "kvh_transcode")
+        out = torch.empty(size, dtype=torch.uint8, device=blob.device)
+    _check(lib().kvh_transcode(blob.data_ptr(), dt, l, n_tokens, c, level_in, level_out, out.data_ptr(), out.numel(),
+                               status.data_ptr() if status is not None else None, _stream_ptr(stream)), "kvh_transcode")
+    return out
+
+
+def make_tc_items(src_ptrs, dst_ptrs, n_tokens, levels_in, levels_out, device) -> torch.Tensor:
+    """Upload an array of kvh_tc_item (argument marshalling; returns a uint8 device tensor)."""
+    a = np.zeros(len(src_ptrs), dtype=TC_ITEM)
+    a["src"], a["dst"], a["n_tokens"], a["level_in"], a["level_out"] = src_ptrs, dst_ptrs, n_tokens, levels_in, levels_out
+    return torch.from_numpy(a.view(np.uint8).copy()).to(device)
+
+
+def transcode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, dtype, l: int, c: int,
+                    status: torch.Tensor | None = None, stream=None) -> None:
+    """kvh_transcode_batch: all items in one launch; `items` comes from make_tc_items."""
+    _require_cuda(items, status)
+    if status is not None and (status.dtype != torch.int32 or status.numel() < n_items):
+        raise ValueError("status must be int32 with one entry per item")
+    _check(lib().kvh_transcode_batch(items.data_ptr(), n_items, max_tokens_per_item, _dt_code(dtype), l, c,
+                                     status.data_ptr() if status is not None else None, _stream_ptr(stream)),
+           "kvh_transcode_batch")
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -234,6 +234,37 @@ int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int
   return launch_decode(a, dt, 1, n, static_cast<hipStream_t>(stream));
 }
 
+int kvh_transcode(const void* src_dev, kvh_dtype dt, int l, int n_tokens, int c, int level_in, int level_out,
+                  void* dst_dev, size_t dst_cap, int32_t* status_dev, void* stream) {
+  if (src_dev == nullptr || dst_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (level_bits(level_in) < 0 || level_bits(level_out) < 0) return KVH_E_LEVEL;
+  if (int rc = check_shape(l, n_tokens, c)) return rc;
+  const size_t size_in = kvh_blob_size(l, n_tokens, c, level_in), size_out = kvh_blob_size(l, n_tokens, c, level_out);
+  if (dst_cap < size_out) return KVH_E_SIZE;
+  if (!aligned16(src_dev) || !aligned16(dst_dev)) return KVH_E_ALIGN;
+  const uintptr_t s = reinterpret_cast<uintptr_t>(src_dev), d = reinterpret_cast<uintptr_t>(dst_dev);
+  if (s < d + size_out && d < s + size_in) return KVH_E_ARG;  // overlapping buffers
+  TranscodeParams a{};
+  a.items = nullptr;
+  a.one = kvh_tc_item{src_dev, dst_dev, n_tokens, level_in, level_out, 0};
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  return launch_transcode(a, dt, 1, n_tokens, static_cast<hipStream_t>(stream));
+}
+
+int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
+                        int32_t* status_dev, void* stream) {
+  if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
+  TranscodeParams a{};
+  a.items = items_dev;
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  return launch_transcode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
 int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
   if (dst_dev == nullptr || src_dev == nullptr || bytes == 0) return KVH_E_ARG;
   if (bytes % 16 != 0 || !aligned16(dst_dev) || !aligned16(src_dev)) return KVH_E_ALIGN;

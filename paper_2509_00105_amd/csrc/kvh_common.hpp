@@ -117,8 +117,16 @@ struct EncodeParams {
 
 constexpr int32_t kNoSplit = 0x7fffffff;
 
+struct TranscodeParams {
+  const kvh_tc_item* items;  // device array of jobs, or nullptr: transcode `one`
+  kvh_tc_item one;
+  int32_t* status;           // nullable; indexed by item
+  int l, c;
+};
+
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
 int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
+int launch_transcode(const TranscodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
 
 #define KVH_HIP_CHECK_LAUNCH()                          \
   do {                                                  \

@@ -1,0 +1,423 @@
+// Level transcoder: re-compress a stored blob from b_in to b_out bits per element without ever
+// writing 16-bit KV to memory (the policy's "compress an entry further" step; Design section,
+// marginal utility drop).  The result is, byte for byte, encode(decode(blob)).
+//
+// Why no statistics pass is needed: in a blob written by the encoder (or by this kernel) every
+// group holds code 0 and code L.  Code 0 decodes to the stored minimum exactly, code L to the
+// stored maximum, and every other code to something in between, so the minimum and maximum of
+// the decoded group are the stored ones and the re-encoded group keeps its metadata word.  The
+// one exception is a degenerate group (range below 2^-100): all its elements decode to the
+// minimum, so its new word is (mn, mn).  With the statistics known up front the kernel is a
+// pure stream: code in -> fp32 reconstruction -> rounding to the 16-bit type -> position in the
+// same range at the new rate -> code out.
+//
+// Block = 8 waves x 16 token rows = one K token-group x a 1024-channel span; a lane owns 16
+// consecutive channels, so a wave moves one whole code row of the span per access (16 / 8 / 4
+// bytes per lane at 8 / 4 / 2 bits).  K parameters (per channel) are prepared once per block,
+// two channels per thread, and shared through LDS; V parameters (per token and head) are
+// prepared by one lane per group and broadcast inside the wave.
+#include <type_traits>
+
+#include "kvh_common.hpp"
+
+namespace kvh {
+
+#ifndef KVH_TC_NT
+#define KVH_TC_NT 1  // non-temporal stores of the output codes
+#endif
+
+constexpr int kTcWaves = 8;
+constexpr int kTcThreads = kTcWaves * kWave;      // 512
+constexpr int kTcLaneCh = 16;                     // channels per lane
+constexpr int kTcSpanCh = kWave * kTcLaneCh;      // 1024 channels per wave access
+constexpr int kTcRows = kGroup / kTcWaves;        // 16 rows per wave
+constexpr int kTcBatch = 8;                       // rows in flight per wave
+constexpr int kTcSpanHeads = kTcSpanCh / kGroup;  // 8 V groups per row of a span
+static_assert(kTcBatch * kTcSpanHeads == kWave, "one lane per V group of a batch");
+static_assert(kTcThreads * 2 == kTcSpanCh, "two K channels per thread");
+
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+template <typename T>
+__device__ __forceinline__ T gload(const uint8_t* p) {
+  return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+template <typename T>
+__device__ __forceinline__ void gstore(uint8_t* p, T v) {
+  *reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)) = v;
+}
+template <typename T>
+__device__ __forceinline__ void gstore_stream(uint8_t* p, T v) {
+#if KVH_TC_NT
+  __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  gstore<T>(p, v);
+#endif
+}
+
+// Two fp32 values -> two 16-bit values in one word, each rounded to nearest even.
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  floatx2 f = {a, b};
+  if constexpr (DT == KVH_F16) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, halfx2));
+  } else {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+  }
+}
+
+// fp32 reconstruction of a code.  The definition rounds twice (fma to fp32, then to the 16-bit
+// type); the empty asm keeps the compiler from merging the two into one mixed-precision fma.
+__device__ __forceinline__ float recon(float q, float scale, float mn) {
+  float y = __builtin_fmaf(q, scale, mn);
+  asm("" : "+v"(y));
+  return y;
+}
+
+// The 16 input codes of a lane, as floats.
+template <int BITS>
+struct InCodes;
+template <>
+struct InCodes<8> {
+  uintx4 w;
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx4>(p); }
+  __device__ __forceinline__ float get(int j) const {
+    const uint32_t v[4] = {w.x, w.y, w.z, w.w};
+    return (float)((v[j >> 2] >> (8 * (j & 3))) & 0xffu);
+  }
+};
+template <>
+struct InCodes<4> {
+  uintx2 w;
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx2>(p); }
+  // nibbles are spread into bytes first, so that each code costs one byte->float convert
+  __device__ __forceinline__ float get(int j) const {
+    const uint32_t v = (j >> 3) ? w.y : w.x;
+    const uint32_t e = ((j & 1) ? v >> 4 : v) & 0x0f0f0f0fu;
+    return (float)((e >> (8 * ((j & 7) >> 1))) & 0xffu);
+  }
+};
+template <>
+struct InCodes<2> {
+  uint32_t w;
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint32_t>(p); }
+  __device__ __forceinline__ float get(int j) const {
+    const uint32_t e = (w >> (2 * (j & 3))) & 0x03030303u;
+    return (float)((e >> (8 * (j >> 2))) & 0xffu);
+  }
+};
+
+// Four positions -> four code bytes in one word; the convert rounds to nearest even and
+// saturates to [0, 255].
+__device__ __forceinline__ uint32_t codes4(float t0, float t1, float t2, float t3) {
+  uint32_t a = __builtin_amdgcn_cvt_pk_u8_f32(t0, 0, 0u);
+  a = __builtin_amdgcn_cvt_pk_u8_f32(t1, 1, a);
+  a = __builtin_amdgcn_cvt_pk_u8_f32(t2, 2, a);
+  return __builtin_amdgcn_cvt_pk_u8_f32(t3, 3, a);
+}
+
+// Pack 16 positions into BITS-bit codes (channel order, LSB first) and store them.
+template <int BITS>
+__device__ __forceinline__ void store_codes16(uint8_t* p, const float (&t)[16]) {
+  uint32_t a[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) a[k] = codes4(t[4 * k], t[4 * k + 1], t[4 * k + 2], t[4 * k + 3]);
+  if constexpr (BITS == 8) {
+    uintx4 o = {a[0], a[1], a[2], a[3]};
+    gstore_stream<uintx4>(p, o);
+  } else if constexpr (BITS == 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      a[k] &= 0x0f0f0f0fu;  // a no-op for finite positions; keeps stray bits inside their field otherwise
+      a[k] |= a[k] >> 4;    // byte 0 = c0 | c1 << 4, byte 2 = c2 | c3 << 4
+    }
+    uintx2 o = {__builtin_amdgcn_perm(a[1], a[0], 0x06040200u), __builtin_amdgcn_perm(a[3], a[2], 0x06040200u)};
+    gstore_stream<uintx2>(p, o);
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      a[k] &= 0x03030303u;
+      a[k] |= a[k] >> 6;
+      a[k] |= a[k] >> 12;  // byte 0 = c0 | c1 << 2 | c2 << 4 | c3 << 6
+    }
+    uint32_t lo = __builtin_amdgcn_perm(a[1], a[0], 0x0c0c0400u);  // bytes 0, 1
+    uint32_t hi = __builtin_amdgcn_perm(a[3], a[2], 0x04000c0cu);  // bytes 2, 3
+    gstore_stream<uint32_t>(p, lo | hi);
+  }
+}
+
+// Everything one group contributes to the arithmetic, as fp32.
+struct TcParams {
+  float mn;     // f32(mn)
+  float scale;  // r / L_in, or 0 (degenerate)
+  float inv;    // L_out / r, or 0 (degenerate)
+  float top;    // what code L_in decodes to: f32(mx), or f32(mn) (degenerate)
+};
+
+// Parameters of a group from its metadata word; also the word the re-encoded group stores and
+// whether code L_in needs the explicit "decode to the stored maximum" rule.
+template <int DT, int BI, int BO>
+__device__ __forceinline__ TcParams tc_params(uint32_t meta, uint32_t& out_meta, bool& fix) {
+  constexpr float LI = float((1 << BI) - 1), LO = float((1 << BO) - 1);
+  TcParams p;
+  const uint32_t mn_bits = meta & 0xffffu, mx_bits = meta >> 16;
+  p.mn = t16_to_f32<DT>(mn_bits);
+  const float r = t16_to_f32<DT>(mx_bits) - p.mn;
+  const bool degenerate = r < 0x1p-100f;
+  p.scale = degenerate ? 0.0f : r / LI;  // IEEE divisions (correctly rounded)
+  p.inv = degenerate ? 0.0f : LO / r;
+  const uint32_t top_bits = degenerate ? mn_bits : mx_bits;
+  p.top = t16_to_f32<DT>(top_bits);
+  out_meta = mn_bits | top_bits << 16;
+  fix = (pack2<DT>(recon(LI, p.scale, p.mn), 0.0f) & 0xffffu) != top_bits;
+  return p;
+}
+
+// One row of a lane: 16 codes in, 16 codes out.  param(j) gives the parameters of channel j.
+template <int DT, int BI, int BO, bool FIX, typename P>
+__device__ __forceinline__ void transcode_row(uint8_t* out, const InCodes<BI>& cw, P&& param) {
+  constexpr float LI = float((1 << BI) - 1);
+  float t[kTcLaneCh];
+#pragma unroll
+  for (int j = 0; j < kTcLaneCh; j += 2) {
+    const TcParams& p0 = param(j);
+    const TcParams& p1 = param(j + 1);
+    const float q0 = cw.get(j), q1 = cw.get(j + 1);
+    const uint32_t pk = pack2<DT>(recon(q0, p0.scale, p0.mn), recon(q1, p1.scale, p1.mn));
+    float x0 = t16_to_f32<DT>(pk & 0xffffu), x1 = t16_to_f32<DT>(pk >> 16);
+    if constexpr (FIX) {
+      x0 = q0 == LI ? p0.top : x0;
+      x1 = q1 == LI ? p1.top : x1;
+    }
+    // position in the range at the new rate: subtract, then multiply (two roundings)
+    t[j] = (x0 - p0.mn) * p0.inv;
+    t[j + 1] = (x1 - p1.mn) * p1.inv;
+  }
+  store_codes16<BO>(out, t);
+}
+
+struct HeaderWords {
+  uintx4 a, b, c;
+};
+
+// Header of the source blob against the call; the token-dropping words are accepted if they are
+// all zero or describe an entry of which exactly n tokens are kept.
+__device__ __forceinline__ bool source_header_ok(const HeaderWords& h, int dt, int bits, int l, int n, int c, size_t total) {
+  const bool fields = h.a.x == kMagic && h.a.y == (1u | (uint32_t)dt << 16 | (uint32_t)bits << 24) && h.a.z == (uint32_t)l &&
+                      h.a.w == (uint32_t)n && h.b.x == (uint32_t)c && h.b.y == ((uint32_t)kGroup | (uint32_t)kGroup << 16) &&
+                      h.b.z == (uint32_t)total && h.b.w == (uint32_t)((uint64_t)total >> 32);
+  const uint32_t orig = h.c.x, sink = h.c.y, window = h.c.z;
+  const uint64_t sw = (uint64_t)sink + window;
+  const bool plain = (orig | sink | window) == 0;
+  const bool dropped = orig >= 1 && orig <= 0x7fffffffu && sw >= 1 && sw <= 0x7fffffffu &&
+                       (sw >= orig ? orig : (uint32_t)sw) == (uint32_t)n;
+  return fields && (plain || dropped);
+}
+
+template <int DT, int BI, int BO>
+__device__ __forceinline__ void transcode_block(const TranscodeParams& a, const kvh_tc_item& it, int item_idx, int lam,
+                                                bool is_v, int g, int span, TcParams* kpar) {
+  using Yes = std::integral_constant<bool, true>;
+  using No = std::integral_constant<bool, false>;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = it.n_tokens;
+  const int c = a.c;
+  const int heads = c / kGroup;
+  const uint8_t* src = static_cast<const uint8_t*>(it.src);
+  uint8_t* dst = static_cast<uint8_t*>(it.dst);
+  const LayerGeom gi = layer_geom(n, c, BI), go = layer_geom(n, c, BO);
+  const HeaderWords hdr = {gload<uintx4>(src), gload<uintx4>(src + 16), gload<uintx4>(src + 32)};
+
+  const int ch_raw = span * kTcSpanCh + lane * kTcLaneCh;
+  const bool active = ch_raw < c;  // idle lanes of a partial span shadow channel 0 and never store
+  const uint32_t ch = active ? (uint32_t)ch_raw : 0u;
+  const int t_first = g * kGroup + wave * kTcRows;
+
+  const uint8_t* in_layer = src + kHeaderBytes + (size_t)lam * gi.layer_bytes();
+  uint8_t* out_layer = dst + kHeaderBytes + (size_t)lam * go.layer_bytes();
+  const uint8_t* in_codes = in_layer + gi.kmeta + (is_v ? gi.codes + gi.vmeta : 0) + ch * BI / 8;
+  uint8_t* out_codes = out_layer + go.kmeta + (is_v ? go.codes + go.vmeta : 0) + ch * BO / 8;
+
+  InCodes<BI> cw[kTcBatch];
+  auto load_batch = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < kTcBatch; ++i) {
+      int t = t0 + i;
+      t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
+      cw[i].load(in_codes + (size_t)t * gi.row_bytes);
+    }
+  };
+  auto run_batch = [&](int t0, auto fix_tag, auto&& param_of) {
+    constexpr bool FIX = decltype(fix_tag)::value;
+#pragma unroll
+    for (int i = 0; i < kTcBatch; ++i) {
+      if (t0 + i < n) {  // wave-uniform
+        auto param = param_of(i);  // may shuffle across lanes: taken with the whole wave enabled
+        if (active) transcode_row<DT, BI, BO, FIX>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[i], param);
+      }
+    }
+  };
+
+  // The caller guarantees kvh_blob_size(l, n_tokens, c, level_in) readable bytes at the source,
+  // so the loads issued before the header verdict stay inside the buffer whatever it says.
+  if (t_first < n) load_batch(t_first);
+
+  uintx2 km = {0u, 0u};
+  const int pc = span * kTcSpanCh + (int)threadIdx.x * 2;  // the two K channels this thread prepares
+  const bool pact = !is_v && pc < c;
+  if (pact) km = gload<uintx2>(in_layer + ((size_t)g * c + pc) * 4);
+
+  // block-uniform verdict: every thread reads the same header
+  if (!source_header_ok(hdr, DT, BI, a.l, n, c, kHeaderBytes + (size_t)a.l * gi.layer_bytes())) {
+    if (a.status != nullptr && threadIdx.x == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
+    return;
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kHeaderBytes / 4) {
+    const uint64_t total = kHeaderBytes + (uint64_t)a.l * go.layer_bytes();
+    uint32_t w = 0;
+    switch (threadIdx.x) {
+      case 0: w = kMagic; break;
+      case 1: w = 1u | (uint32_t)DT << 16 | (uint32_t)BO << 24; break;
+      case 2: w = (uint32_t)a.l; break;
+      case 3: w = (uint32_t)n; break;
+      case 4: w = (uint32_t)c; break;
+      case 5: w = (uint32_t)kGroup | (uint32_t)kGroup << 16; break;
+      case 6: w = (uint32_t)total; break;
+      case 7: w = (uint32_t)(total >> 32); break;
+      case 8: w = hdr.c.x; break;  // token-dropping words are carried over
+      case 9: w = hdr.c.y; break;
+      case 10: w = hdr.c.z; break;
+      default: break;
+    }
+    gstore<uint32_t>(dst + 4 * threadIdx.x, w);
+  }
+
+  if (!is_v) {
+    bool fix = false;
+    uint32_t om[2] = {0u, 0u};
+    const uint32_t meta[2] = {km.x, km.y};
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      bool f;
+      const TcParams p = tc_params<DT, BI, BO>(meta[e], om[e], f);
+      fix |= pact && f;
+      const int lc = (int)threadIdx.x * 2 + e;  // channel within the span; its user is lane lc / 16, slot lc % 16
+      kpar[(lc % kTcLaneCh) * kWave + lc / kTcLaneCh] = p;
+    }
+    if (pact) {
+      uintx2 o = {om[0], om[1]};
+      gstore<uintx2>(out_layer + ((size_t)g * c + pc) * 4, o);
+    }
+    const bool any_fix = __syncthreads_or(fix);
+    if (t_first >= n) return;  // wave-uniform, after the barrier
+    TcParams p[kTcLaneCh];
+#pragma unroll
+    for (int j = 0; j < kTcLaneCh; ++j) p[j] = kpar[j * kWave + lane];
+    auto param_of = [&](int) { return [&p](int j) -> const TcParams& { return p[j]; }; };
+#pragma unroll 1
+    for (int t0 = t_first;;) {
+      if (any_fix) run_batch(t0, Yes{}, param_of); else run_batch(t0, No{}, param_of);
+      t0 += kTcBatch;
+      if (t0 >= t_first + kTcRows || t0 >= n) break;
+      load_batch(t0);
+    }
+  } else {
+    if (t_first >= n) return;  // wave-uniform; V waves never meet at a barrier
+    const uint8_t* in_vmeta = in_layer + gi.kmeta + gi.codes;
+    uint8_t* out_vmeta = out_layer + go.kmeta + go.codes;
+#pragma unroll 1
+    for (int t0 = t_first;;) {
+      // lane -> the group (row t0 + lane / 8, head lane % 8 of this span)
+      const int t = t0 + lane / kTcSpanHeads;
+      const int head = span * kTcSpanHeads + lane % kTcSpanHeads;
+      TcParams mine = {0.0f, 0.0f, 0.0f, 0.0f};
+      bool fix = false;
+      if (t < n && head < heads) {
+        const size_t off = ((size_t)t * heads + head) * 4;
+        uint32_t om;
+        mine = tc_params<DT, BI, BO>(gload<uint32_t>(in_vmeta + off), om, fix);
+        gstore<uint32_t>(out_vmeta + off, om);
+      }
+      const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+      auto param_of = [&](int i) {
+        const int owner = i * kTcSpanHeads + lane / (kGroup / kTcLaneCh);
+        TcParams p;
+        p.mn = __shfl(mine.mn, owner);
+        p.scale = __shfl(mine.scale, owner);
+        p.inv = __shfl(mine.inv, owner);
+        p.top = __shfl(mine.top, owner);
+        return [p](int) -> const TcParams& { return p; };
+      };
+      if (any_fix) run_batch(t0, Yes{}, param_of); else run_batch(t0, No{}, param_of);
+      t0 += kTcBatch;
+      if (t0 >= t_first + kTcRows || t0 >= n) break;
+      load_batch(t0);
+    }
+    // zero the padding that rounds the vmeta section up to 16 bytes
+    if (span == 0 && threadIdx.x == 0 && (g + 1) * kGroup >= n) {
+      for (size_t o = (size_t)n * heads * 4; o < go.vmeta; o += 4) gstore<uint32_t>(out_vmeta + o, 0u);
+    }
+  }
+}
+
+}  // namespace
+
+// grid = (token-groups x spans, 2 * l, items)
+template <int DT>
+__global__ __launch_bounds__(kTcThreads) void transcode_kernel(TranscodeParams a) {
+  __shared__ TcParams kpar[kTcLaneCh * kWave];  // 16 KiB, [slot][lane]
+  kvh_tc_item it;
+  if (a.items != nullptr) {
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + blockIdx.z);
+    uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16);
+    it.src = reinterpret_cast<const void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
+    it.dst = reinterpret_cast<void*>((uint64_t)lo.z | (uint64_t)lo.w << 32);
+    it.n_tokens = (int32_t)hi.x;
+    it.level_in = (int32_t)hi.y;
+    it.level_out = (int32_t)hi.z;
+    it.reserved = 0;
+  } else {
+    it = a.one;
+  }
+  const int nspans = (a.c + kTcSpanCh - 1) / kTcSpanCh;
+  const int g = blockIdx.x / nspans;
+  const int span = blockIdx.x - g * nspans;
+  if (it.n_tokens < 1 || g * kGroup >= it.n_tokens) return;  // block-uniform
+  const int lam = blockIdx.y >> 1;
+  const bool is_v = blockIdx.y & 1;
+  const int bi = level_bits(it.level_in), bo = level_bits(it.level_out);
+  if (bi < 0 || bo < 0) {
+    if (a.status != nullptr && threadIdx.x == 0) a.status[blockIdx.z] = KVH_DEV_HEADER_MISMATCH;
+    return;
+  }
+#define KVH_TC_CASE(BI, BO) \
+  case BI * 16 + BO: transcode_block<DT, BI, BO>(a, it, blockIdx.z, lam, is_v, g, span, kpar); break;
+  switch (bi * 16 + bo) {
+    KVH_TC_CASE(8, 8) KVH_TC_CASE(8, 4) KVH_TC_CASE(8, 2)
+    KVH_TC_CASE(4, 8) KVH_TC_CASE(4, 4) KVH_TC_CASE(4, 2)
+    KVH_TC_CASE(2, 8) KVH_TC_CASE(2, 4) KVH_TC_CASE(2, 2)
+    default: break;
+  }
+#undef KVH_TC_CASE
+}
+
+int launch_transcode(const TranscodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
+  const int nspans = (a.c + kTcSpanCh - 1) / kTcSpanCh;
+  const int groups = (max_tokens + kGroup - 1) / kGroup;
+  dim3 grid((unsigned)(groups * nspans), (unsigned)(2 * a.l), (unsigned)n_items);
+  if (dt == KVH_F16)
+    hipLaunchKernelGGL(transcode_kernel<KVH_F16>, grid, dim3(kTcThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL(transcode_kernel<KVH_BF16>, grid, dim3(kTcThreads), 0, stream, a);
+  KVH_HIP_CHECK_LAUNCH();
+  return KVH_OK;
+}
+
+}  // namespace kvh

@@ -34,7 +34,8 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert set(names) >= {"kvh_encode", "kvh_decode", "kvh_encode_batch", "kvh_decode_batch", "kvh_encode_chunked",
-                          "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe"}
+                          "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe",
+                          "kvh_kept_tokens", "kvh_encode_kept", "kvh_decode_kept", "kvh_transcode", "kvh_transcode_batch"}
     for n in names:
         assert hasattr(lib, n), n
 
@@ -110,6 +111,36 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.kvh_decode_batch(None, 1, 256, 0, 1, 1024, v, 16, None, None) == E_ARG
     assert lib.kvh_decode_batch(P, 1, 256, 0, 1, 1024, v, 0, None, None) == E_ARG
     assert lib.kvh_decode_batch(P, 1, 0, 0, 1, 1024, v, 16, None, None) == E_SHAPE
+
+    kept_e, kept_d = lib.kvh_encode_kept, lib.kvh_decode_kept
+    assert lib.kvh_kept_tokens(10, 2, 3) == 5 and lib.kvh_kept_tokens(10, 0, 0) == 0 and lib.kvh_kept_tokens(0, 1, 1) == 0
+    assert lib.kvh_kept_tokens(10, 2**31 - 1, 2**31 - 1) == 10
+    assert kept_e(v, 0, 1, 256, 1024, 0, 0, 0, P, big, None) == E_SHAPE      # nothing kept
+    assert kept_e(v, 0, 1, 256, 1024, -1, 8, 0, P, big, None) == E_SHAPE
+    assert kept_e(v, 0, 1, 256, 1024, 4, 60, 5, P, big, None) == E_LEVEL
+    assert kept_e(v, 0, 1, 256, 1024, 4, 60, 0, P, lib.kvh_blob_size(1, 64, 1024, 0) - 1, None) == E_SIZE
+    assert kept_e(v, 0, 1, 256, 1024, 4, 60, 0, P + 4, big, None) == E_ALIGN
+    assert kept_d(None, 0, 1, 256, 1024, 4, 60, 0, v, 0, 0, None, 16, None, None) == E_ARG
+    assert kept_d(P, 0, 1, 256, 1024, 0, 0, 0, v, 0, 0, None, 16, None, None) == E_SHAPE
+    assert kept_d(P, 0, 1, 256, 1024, 4, 60, 0, v, 0, 0, P, 0, None, None) == E_ARG
+    assert kept_d(P, 0, 1, 256, 1024, 4, 60, 0, v, 2**31 - 100, 0, None, 16, None, None) == E_ARG
+
+    tc = lib.kvh_transcode
+    Q = P + (1 << 30)
+    assert tc(None, 0, 1, 128, 1024, 0, 2, Q, big, None, None) == E_ARG
+    assert tc(P, 0, 1, 128, 1024, 0, 2, None, big, None, None) == E_ARG
+    assert tc(P, 5, 1, 128, 1024, 0, 2, Q, big, None, None) == E_ARG
+    assert tc(P, 0, 1, 128, 1024, 3, 2, Q, big, None, None) == E_LEVEL
+    assert tc(P, 0, 1, 128, 1024, 0, -1, Q, big, None, None) == E_LEVEL
+    assert tc(P, 0, 1, 128, 1000, 0, 2, Q, big, None, None) == E_SHAPE
+    assert tc(P, 0, 1, 128, 1024, 0, 2, Q, lib.kvh_blob_size(1, 128, 1024, 2) - 1, None, None) == E_SIZE
+    assert tc(P + 8, 0, 1, 128, 1024, 0, 2, Q, big, None, None) == E_ALIGN
+    assert tc(P, 0, 1, 128, 1024, 0, 2, Q + 8, big, None, None) == E_ALIGN
+    assert tc(P, 0, 1, 128, 1024, 0, 2, P + 4096, big, None, None) == E_ARG   # destination inside the source blob
+    assert tc(P + 4096, 0, 1, 128, 1024, 0, 2, P, big, None, None) == E_ARG   # source inside the destination blob
+    assert lib.kvh_transcode_batch(None, 1, 256, 0, 1, 1024, None, None) == E_ARG
+    assert lib.kvh_transcode_batch(P, 0, 256, 0, 1, 1024, None, None) == E_ARG
+    assert lib.kvh_transcode_batch(P, 1, 256, 0, 1, 1000, None, None) == E_SHAPE
     assert lib.kvh_copy_probe(P, P + 4096, 100, None) == E_ALIGN
     assert lib.kvh_copy_probe(None, P, 4096, None) == E_ARG
 

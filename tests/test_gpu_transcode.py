@@ -1,0 +1,202 @@
+"""GPU parity of the fused transcode (kvh_transcode / kvh_transcode_batch) against the CPU oracle, whose
+transcode is decode followed by encode.  Bar: output blobs byte for byte.  Source blobs are the ORACLE's,
+so a transcoder fault cannot hide behind an encoder fault."""
+import struct
+
+import numpy as np
+import pytest
+
+import kv_inputs as gen
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = gen.F16, gen.BF16
+PAIRS = [(a, b) for a in range(3) for b in range(3)]
+
+
+@pytest.fixture(scope="module")
+def kvh():
+    import paper_2509_00105_amd as m
+
+    m.lib()
+    return m
+
+
+def assert_same_blob(got: np.ndarray, want: np.ndarray, what: str):
+    assert got.size == want.size, (what, got.size, want.size)
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero(got != want)
+        raise AssertionError("%s: %d of %d blob bytes differ; first at offset %d: got 0x%02x want 0x%02x"
+                             % (what, bad.size, got.size, bad[0], got[bad[0]], want[bad[0]]))
+
+
+SHAPES = [
+    (1, 1, 128),      # a single token: one-element K groups (all degenerate)
+    (2, 300, 256),    # ragged last K group (44 tokens); a quarter of a span
+    (3, 130, 384),    # vmeta needs padding (130 * 3 * 4 = 1560 bytes)
+    (2, 257, 1024),   # one full span, one token past two groups
+    (1, 515, 1152),   # a full span and an eighth of the next; several groups and a tail
+    (1, 72, 2048),    # two spans, partial batch of rows
+]
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_transcode_matches_oracle(kvh, shape, dt):
+    l, n, c = shape
+    k, v = gen.make_kv(l, n, c, dt, seed=300 + l + n + c)
+    for a, b in PAIRS:
+        src = oracle.encode(k, v, dt, a)
+        want = oracle.transcode(src, dt, l, n, c, a, b)
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = torch.full((want.size + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+        kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, a, b, out=out, status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        got = out.cpu().numpy()
+        assert_same_blob(got[: want.size], want, "transcode %s %d->%d" % (shape, a, b))
+        assert (got[want.size:] == 0xAB).all()  # nothing written past the blob
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+def test_transcode_special_groups(kvh, dt):
+    """Constant groups, 1-ulp ranges, tiny max against a wide range (the explicit top-code rule), signed zeros,
+    degenerate bf16 ranges: as K groups (along tokens) and V groups (along channels)."""
+    p = 10 if dt == F16 else 7
+    rows = []
+    for base in (2.0 ** -6, 1.0, 32.0):
+        rows += [np.full(128, base), np.linspace(base, 2 * base, 128),
+                 np.where(np.arange(128) % 2 == 0, base, base * (1 + 2.0 ** -p)),
+                 base * (1 + np.arange(128) % 4 * 2.0 ** -p),
+                 np.concatenate([[-base * 1000, base * 2.0 ** -9], np.linspace(-base * 1000, 0, 126)]),
+                 np.concatenate([[-1.0, 2.0], np.tile([-0.5, 0.25, 0.5, 1.25], 32)[:126]]) * base,
+                 np.concatenate([[0.0, 15.0], np.tile([7.5, 8.5, 3.0, 0.5, 1.5, 2.5], 21)]) * base]
+    rows += [np.zeros(128), -np.zeros(128), np.where(np.arange(128) % 2 == 0, 0.0, -0.0)]
+    xb = gen._cast_to_bits(np.stack(rows).astype(np.float32), dt)
+    if dt == BF16:
+        extra = np.full((2, 128), 0x0800, dtype=np.uint16)  # 2^-111 with one 2^-110: range below 2^-100
+        extra[0, 5] = 0x0880
+        extra[1] = np.arange(128).astype(np.uint16)          # bf16 subnormals
+        xb = np.concatenate([xb, extra])
+    G = xb.shape[0]
+    v = np.ascontiguousarray(np.broadcast_to(xb[None], (2, G, 128)))
+    k = np.zeros((2, 128, 128), dtype=np.uint16)
+    k[:, :, :G] = xb.T[None]
+    for name, t, n in (("groups along tokens", k, 128), ("groups along channels", v, G)):
+        for a, b in PAIRS:
+            src = oracle.encode(t, t, dt, a)
+            want = oracle.transcode(src, dt, 2, n, 128, a, b)
+            out = kvh.transcode(torch.from_numpy(src).cuda(), dt, 2, n, 128, a, b)
+            torch.cuda.synchronize()
+            assert_same_blob(out.cpu().numpy(), want, "%s %d->%d" % (name, a, b))
+
+
+def test_transcode_of_gpu_blobs_and_chains(kvh):
+    """Blobs written by the GPU encoder, then 8 -> 4 -> 2 on the GPU, each step against the oracle's."""
+    dt, l, n, c = BF16, 2, 384, 1024
+    k, v = gen.make_kv(l, n, c, dt, seed=11)
+    kd = torch.from_numpy(k.view(np.int16)).cuda().view(torch.bfloat16)
+    vd = torch.from_numpy(v.view(np.int16)).cuda().view(torch.bfloat16)
+    b8 = kvh.encode(kd, vd, 0)
+    b4 = kvh.transcode(b8, torch.bfloat16, l, n, c, 0, 1)
+    b2 = kvh.transcode(b4, torch.bfloat16, l, n, c, 1, 2)
+    same = kvh.transcode(b2, torch.bfloat16, l, n, c, 2, 2)
+    torch.cuda.synchronize()
+    w8 = oracle.encode(k, v, dt, 0)
+    w4 = oracle.transcode(w8, dt, l, n, c, 0, 1)
+    w2 = oracle.transcode(w4, dt, l, n, c, 1, 2)
+    assert_same_blob(b8.cpu().numpy(), w8, "encode")
+    assert_same_blob(b4.cpu().numpy(), w4, "8->4")
+    assert_same_blob(b2.cpu().numpy(), w2, "4->2")
+    assert_same_blob(same.cpu().numpy(), w2, "2->2 is the identity")
+    # and the transcoded blob decodes on the GPU to what the oracle decodes
+    wk, wv = oracle.decode(w2, dt, l, n, c, 2)
+    ok = torch.zeros((l, n, c), dtype=torch.bfloat16, device="cuda"); ov = torch.zeros_like(ok)
+    kvh.decode(b2, 2, n, ok, ov)
+    torch.cuda.synchronize()
+    assert np.array_equal(ok.view(torch.int16).cpu().numpy().view(np.uint16), wk)
+    assert np.array_equal(ov.view(torch.int16).cpu().numpy().view(np.uint16), wv)
+
+
+def test_transcode_batch_mixed_items(kvh):
+    """One launch over items of mixed lengths and level pairs, plus one item with a wrong level_in and one skipped."""
+    dt, l, c = F16, 2, 1024
+    rng = np.random.default_rng(5)
+    lens = [256, 130, 1, 384, 256, 77]
+    pairs = [(0, 2), (0, 1), (1, 2), (2, 0), (1, 1), (0, 2)]
+    srcs, wants, outs = [], [], []
+    for i, (n, (a, b)) in enumerate(zip(lens, pairs)):
+        k, v = gen.make_kv(l, n, c, dt, seed=40 + i)
+        s = oracle.encode(k, v, dt, a)
+        srcs.append(torch.from_numpy(s).cuda())
+        wants.append(oracle.transcode(s, dt, l, n, c, a, b))
+        outs.append(torch.full((wants[-1].size,), 0xCD, dtype=torch.uint8, device="cuda"))
+    # item 6: stored at level 0 but claimed to be level 1 -> header mismatch, nothing written; item 7: n_tokens 0 -> skipped
+    srcs += [srcs[0], srcs[0]]
+    outs += [torch.full((wants[0].size,), 0xCD, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    n_tok = lens + [256, 0]
+    lin = [a for a, _ in pairs] + [1, 0]
+    lout = [b for _, b in pairs] + [2, 2]
+    items = kvh.make_tc_items([s.data_ptr() for s in srcs], [o.data_ptr() for o in outs], n_tok, lin, lout, "cuda")
+    status = torch.zeros(len(srcs), dtype=torch.int32, device="cuda")
+    kvh.transcode_batch(items, len(srcs), max(lens), dt, l, c, status=status)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0] * 6 + [1, 0]
+    for i in range(6):
+        assert_same_blob(outs[i].cpu().numpy(), wants[i], "item %d" % i)
+    assert (outs[6].cpu().numpy() == 0xCD).all() and (outs[7].cpu().numpy() == 0xCD).all()
+
+
+def test_transcode_carries_token_dropping_words_and_checks_headers(kvh):
+    dt, l, N, c, sink, window = BF16, 2, 500, 256, 4, 200
+    k, v = gen.make_kv(l, N, c, dt, seed=8)
+    n = oracle.kept_tokens(N, sink, window)
+    src = oracle.encode_kept(k, v, dt, sink, window, 0)
+    want = oracle.transcode(src, dt, l, n, c, 0, 2)
+    assert struct.unpack_from("<III", want, 32) == (N, sink, window)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, 0, 2, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    assert_same_blob(out.cpu().numpy(), want, "token-dropped blob")
+    # the result decodes with decode_kept on the GPU
+    wk = np.zeros((l, N, c), np.uint16); wv = np.zeros_like(wk)
+    assert oracle.decode_kept_into(want, dt, l, N, c, sink, window, 2, wk, wv) == 0
+    ok = torch.zeros((l, N, c), dtype=torch.bfloat16, device="cuda"); ov = torch.zeros_like(ok)
+    kvh.decode_kept(out, 2, N, sink, window, ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    assert np.array_equal(ok.view(torch.int16).cpu().numpy().view(np.uint16), wk)
+    # inconsistent drop words, wrong dtype, wrong token count: status set, destination untouched
+    for what, blob, args in (("drop words", None, (dt, l, n, c)), ("dtype", src, (F16, l, n, c)), ("tokens", src, (dt, l, n - 1, c))):
+        b = src.copy()
+        if what == "drop words":
+            struct.pack_into("<I", b, 36, sink + 1)
+        status.zero_()
+        dst = torch.full((want.size,), 0x5A, dtype=torch.uint8, device="cuda")
+        kvh.transcode(torch.from_numpy(b).cuda(), args[0], args[1], args[2], args[3], 0, 2, out=dst, status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 1, what
+        assert (dst.cpu().numpy() == 0x5A).all(), what
+
+
+def test_transcode_argument_errors(kvh):
+    dt, l, n, c = F16, 1, 128, 128
+    k, v = gen.make_kv(l, n, c, dt, seed=2)
+    src = torch.from_numpy(oracle.encode(k, v, dt, 0)).cuda()
+    out = torch.empty(kvh.blob_size(l, n, c, 2), dtype=torch.uint8, device="cuda")
+    with pytest.raises(kvh.KVHError):
+        kvh.transcode(src, dt, l, n, c, 0, 3, out=out)
+    with pytest.raises(kvh.KVHError):
+        kvh.transcode(src, dt, l, n, c, 0, 2, out=out[:-16])
+    with pytest.raises(kvh.KVHError):
+        kvh.transcode(src, dt, l, n, 100, 0, 2, out=out)
+    with pytest.raises(kvh.KVHError):
+        kvh.transcode(src, dt, l, n, c, 0, 0, out=src)  # overlapping buffers
+    with pytest.raises(kvh.KVHError):
+        kvh.transcode(src[1:], dt, l, n, c, 0, 2, out=out)  # misaligned
+    with pytest.raises(ValueError):
+        kvh.transcode(src.cpu(), dt, l, n, c, 0, 2)
+    torch.cuda.synchronize()
