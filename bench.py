@@ -187,6 +187,30 @@ def main():
                                  "kept_uncompressed_GBps": kept_bytes / ms / 1e6,
                                  "hbm_frac": (kept_bytes + kblob.numel()) / ms / 1e6 / HBM_PEAK_GBPS})
         assert int(st1.item()) == 0
+
+    # Also outside the timed region: the fused transcode (re-compress stored blobs to a lower level without
+    # materialising 16-bit KV) over the same 32 chunks, for the three downward level pairs, run in rotation so
+    # that no launch finds its input in the last-level cache.  `unfused_ms` is what decode + encode of the same
+    # pair cost in the timed region above.
+    tc_pairs = [(0, 1), (0, 2), (1, 2)]
+    tc_out, tc_items, tc_status = {}, {}, {}
+    for a, b in tc_pairs:
+        size_a, size_b = kvh.blob_size(l, chunk, c, a), kvh.blob_size(l, chunk, c, b)
+        tc_out[(a, b)] = torch.empty(n_chunks * size_b, dtype=torch.uint8, device=dev)
+        tc_items[(a, b)] = kvh.make_tc_items([blobs[a].data_ptr() + i * size_a for i in range(n_chunks)],
+                                             [tc_out[(a, b)].data_ptr() + i * size_b for i in range(n_chunks)],
+                                             [chunk] * n_chunks, [a] * n_chunks, [b] * n_chunks, dev)
+        tc_status[(a, b)] = torch.zeros(n_chunks, dtype=torch.int32, device=dev)
+    tc_reps = 10
+    with torch.cuda.stream(stream):
+        tev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(tc_pairs) + 1)] for _ in range(tc_reps + 1)]
+        for r in range(tc_reps + 1):  # rep 0 is the warm-up
+            tev[r][0].record(stream)
+            for j, pr in enumerate(tc_pairs):
+                kvh.transcode_batch(tc_items[pr], n_chunks, chunk, tdt, l, c, status=tc_status[pr], stream=stream)
+                tev[r][j + 1].record(stream)
+        torch.cuda.synchronize()
+    assert all(int(tc_status[pr].abs().sum().item()) == 0 for pr in tc_pairs), "a transcode reported a header mismatch"
     step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
@@ -203,6 +227,17 @@ def main():
                            "hbm_GBps": (u + b) / avg / 1e6, "hbm_frac": (u + b) / avg / 1e6 / HBM_PEAK_GBPS,
                            "traffic": MEASURED_TRAFFIC_BYTES.get((kind, bits)) if args.workload == "llama3_8b_8k" else None})
     dominant = max(per_kernel, key=lambda r: r["avg_ms"])
+    by_op = {(r["op"], r["bits"]): r["avg_ms"] for r in per_kernel}
+    transcode = []
+    for j, (a, b) in enumerate(tc_pairs):
+        durs = [tev[r][j].elapsed_time(tev[r][j + 1]) for r in range(1, tc_reps + 1)]
+        avg = sum(durs) / len(durs)
+        ba, bb = kvh.level_bits(a), kvh.level_bits(b)
+        moved = blobs[a].numel() + tc_out[(a, b)].numel()
+        transcode.append({"kernel": "transcode_kernel", "bits_in": ba, "bits_out": bb, "avg_ms": avg, "min_ms": min(durs),
+                          "algorithmic_bytes": moved, "hbm_frac": moved / avg / 1e6 / HBM_PEAK_GBPS,
+                          "elements_per_s": 2 * l * N * c / avg * 1e3,
+                          "unfused_ms": by_op[("decode", ba)] + by_op[("encode", bb)]})
     dec2 = [r for r in per_kernel if r["op"] == "decode"]
 
     result = {
@@ -223,6 +258,7 @@ def main():
         "kernels": per_kernel,
         "copy_probe_GBps": copy_gbps,
         "token_dropping": dropping,
+        "transcode": transcode,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),
     }
@@ -241,6 +277,15 @@ def main():
         base, parity = cpu_baseline(host_chunks, dt, l, chunk, c, gpu_blobs)
         result["cpu_baseline"] = base
         result["sampled_blobs_match_oracle"] = bool(parity)
+        # one chunk of each transcoded pair against the oracle's decode-then-encode (not part of the timed baseline)
+        import oracle
+        ok = True
+        for a, b in tc_pairs:
+            size_a, size_b = kvh.blob_size(l, chunk, c, a), kvh.blob_size(l, chunk, c, b)
+            ci = picks[-1]
+            want = oracle.transcode(blobs[a][ci * size_a:(ci + 1) * size_a].cpu().numpy(), dt, l, chunk, c, a, b)
+            ok = ok and bool(np.array_equal(want, tc_out[(a, b)][ci * size_b:(ci + 1) * size_b].cpu().numpy()))
+        result["sampled_transcode_matches_oracle"] = ok
     print(json.dumps(result))
 
 

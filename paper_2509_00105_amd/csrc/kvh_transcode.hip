@@ -26,6 +26,15 @@ namespace kvh {
 #define KVH_TC_NT 1  // non-temporal stores of the output codes
 #endif
 
+#ifndef KVH_TC_WPE
+#define KVH_TC_WPE 4  // waves per SIMD the register allocation is held to (0 = compiler's choice): two blocks per CU
+#endif
+#if KVH_TC_WPE
+#define KVH_TC_OCC __attribute__((amdgpu_waves_per_eu(KVH_TC_WPE, KVH_TC_WPE)))
+#else
+#define KVH_TC_OCC
+#endif
+
 constexpr int kTcWaves = 8;
 constexpr int kTcThreads = kTcWaves * kWave;      // 512
 constexpr int kTcLaneCh = 16;                     // channels per lane
@@ -245,29 +254,37 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
   const uint8_t* in_codes = in_layer + gi.kmeta + (is_v ? gi.codes + gi.vmeta : 0) + ch * BI / 8;
   uint8_t* out_codes = out_layer + go.kmeta + (is_v ? go.codes + go.vmeta : 0) + ch * BO / 8;
 
+  // Rows in flight per wave.  A K wave also holds the parameters of its 16 channels (48 registers),
+  // so with 8-bit input (4 registers per row) it takes half as many rows at a time.
+  constexpr int kRowsK = BI == 8 ? kTcBatch / 2 : kTcBatch;
   InCodes<BI> cw[kTcBatch];
-  auto load_batch = [&](int t0) {
+  auto load_batch = [&](int t0, auto rows_tag) {
 #pragma unroll
-    for (int i = 0; i < kTcBatch; ++i) {
+    for (int i = 0; i < decltype(rows_tag)::value; ++i) {
       int t = t0 + i;
       t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
       cw[i].load(in_codes + (size_t)t * gi.row_bytes);
     }
   };
-  auto run_batch = [&](int t0, auto fix_tag, auto&& param_of) {
+  auto run_batch = [&](int t0, auto rows_tag, auto fix_tag, auto&& param_of) {
     constexpr bool FIX = decltype(fix_tag)::value;
 #pragma unroll
-    for (int i = 0; i < kTcBatch; ++i) {
+    for (int i = 0; i < decltype(rows_tag)::value; ++i) {
       if (t0 + i < n) {  // wave-uniform
         auto param = param_of(i);  // may shuffle across lanes: taken with the whole wave enabled
         if (active) transcode_row<DT, BI, BO, FIX>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[i], param);
       }
+      __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the temporaries of different rows apart
     }
   };
+  using RowsK = std::integral_constant<int, kRowsK>;
+  using RowsV = std::integral_constant<int, kTcBatch>;
 
   // The caller guarantees kvh_blob_size(l, n_tokens, c, level_in) readable bytes at the source,
   // so the loads issued before the header verdict stay inside the buffer whatever it says.
-  if (t_first < n) load_batch(t_first);
+  if (t_first < n) {
+    if (is_v) load_batch(t_first, RowsV{}); else load_batch(t_first, RowsK{});
+  }
 
   uintx2 km = {0u, 0u};
   const int pc = span * kTcSpanCh + (int)threadIdx.x * 2;  // the two K channels this thread prepares
@@ -317,17 +334,29 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
     }
     const bool any_fix = __syncthreads_or(fix);
     if (t_first >= n) return;  // wave-uniform, after the barrier
-    TcParams p[kTcLaneCh];
+    // The common path never touches `top`; reading it only where the rule is needed keeps that path's
+    // register count down.
+    auto k_rows = [&](auto fix_tag) {
+      constexpr bool FIX = decltype(fix_tag)::value;
+      TcParams p[kTcLaneCh];
 #pragma unroll
-    for (int j = 0; j < kTcLaneCh; ++j) p[j] = kpar[j * kWave + lane];
-    auto param_of = [&](int) { return [&p](int j) -> const TcParams& { return p[j]; }; };
+      for (int j = 0; j < kTcLaneCh; ++j) {
+        const TcParams& s = kpar[j * kWave + lane];
+        p[j].mn = s.mn;
+        p[j].scale = s.scale;
+        p[j].inv = s.inv;
+        p[j].top = FIX ? s.top : 0.0f;
+      }
+      auto param_of = [&](int) { return [&p](int j) -> const TcParams& { return p[j]; }; };
 #pragma unroll 1
-    for (int t0 = t_first;;) {
-      if (any_fix) run_batch(t0, Yes{}, param_of); else run_batch(t0, No{}, param_of);
-      t0 += kTcBatch;
-      if (t0 >= t_first + kTcRows || t0 >= n) break;
-      load_batch(t0);
-    }
+      for (int t0 = t_first;;) {
+        run_batch(t0, RowsK{}, fix_tag, param_of);
+        t0 += kRowsK;
+        if (t0 >= t_first + kTcRows || t0 >= n) break;
+        load_batch(t0, RowsK{});
+      }
+    };
+    if (any_fix) k_rows(Yes{}); else k_rows(No{});
   } else {
     if (t_first >= n) return;  // wave-uniform; V waves never meet at a barrier
     const uint8_t* in_vmeta = in_layer + gi.kmeta + gi.codes;
@@ -355,10 +384,10 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
         p.top = __shfl(mine.top, owner);
         return [p](int) -> const TcParams& { return p; };
       };
-      if (any_fix) run_batch(t0, Yes{}, param_of); else run_batch(t0, No{}, param_of);
+      if (any_fix) run_batch(t0, RowsV{}, Yes{}, param_of); else run_batch(t0, RowsV{}, No{}, param_of);
       t0 += kTcBatch;
       if (t0 >= t_first + kTcRows || t0 >= n) break;
-      load_batch(t0);
+      load_batch(t0, RowsV{});
     }
     // zero the padding that rounds the vmeta section up to 16 bytes
     if (span == 0 && threadIdx.x == 0 && (g + 1) * kGroup >= n) {
@@ -371,7 +400,7 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
 
 // grid = (token-groups x spans, 2 * l, items)
 template <int DT>
-__global__ __launch_bounds__(kTcThreads) void transcode_kernel(TranscodeParams a) {
+__global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(TranscodeParams a) {
   __shared__ TcParams kpar[kTcLaneCh * kWave];  // 16 KiB, [slot][lane]
   kvh_tc_item it;
   if (a.items != nullptr) {
