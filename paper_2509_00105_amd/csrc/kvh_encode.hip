@@ -72,32 +72,29 @@ __device__ __forceinline__ uint32_t codes4(float t0, float t1, float t2, float t
   return __builtin_amdgcn_cvt_pk_u8_f32(t3, 3, a);
 }
 
+// Two positions -> two code bytes (bytes 0 and 1 of the result).
+__device__ __forceinline__ uint32_t codes2(float t0, float t1) {
+  return __builtin_amdgcn_cvt_pk_u8_f32(t1, 1, __builtin_amdgcn_cvt_pk_u8_f32(t0, 0, 0u));
+}
+
 // Quantise 8 elements and store the BITS bytes they occupy (LSB-first packing).
-// param(j) returns {mn, inv} of channel j.
+// param(j) returns {mn, inv} of channel j.  The convert puts a code into any byte of a word, so
+// narrow codes are routed at that point: word i receives, in its byte k, the code that belongs i
+// fields above the bottom of output byte k, and the words are merged with one shift-or each.
+// (For finite input every code is <= L, so fields never overlap.)
 template <int BITS, typename P>
 __device__ __forceinline__ void quantise_store8(uint8_t* p, const float (&x)[8], P&& param) {
   float t[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) t[j] = position(x[j], param(j).x, param(j).y);
-  uint32_t a = codes4(t[0], t[1], t[2], t[3]);
-  uint32_t b = codes4(t[4], t[5], t[6], t[7]);
   if constexpr (BITS == 8) {
-    uintx2 w = {a, b};
+    uintx2 w = {codes4(t[0], t[1], t[2], t[3]), codes4(t[4], t[5], t[6], t[7])};
     gstore<uintx2>(p, w);
   } else if constexpr (BITS == 4) {
-    a &= 0x0f0f0f0fu;  // no-ops for finite input; keep stray bits of unspecified codes inside their field
-    b &= 0x0f0f0f0fu;
-    a |= a >> 4;       // byte 0 = c0 | c1 << 4, byte 2 = c2 | c3 << 4
-    b |= b >> 4;
-    gstore<uint32_t>(p, __builtin_amdgcn_perm(b, a, 0x06040200u));
+    gstore<uint32_t>(p, codes4(t[0], t[2], t[4], t[6]) | codes4(t[1], t[3], t[5], t[7]) << 4);
   } else {
-    a &= 0x03030303u;
-    b &= 0x03030303u;
-    a |= a >> 6;       // byte 0 = c0 | c1 << 2, byte 2 = c2 | c3 << 2
-    b |= b >> 6;
-    a |= a >> 12;      // byte 0 = c0 | c1 << 2 | c2 << 4 | c3 << 6
-    b |= b >> 12;
-    gstore<uint16_t>(p, (uint16_t)__builtin_amdgcn_perm(b, a, 0x0c0c0400u));
+    gstore<uint16_t>(p, (uint16_t)(codes2(t[0], t[4]) | codes2(t[1], t[5]) << 2 | codes2(t[2], t[6]) << 4 |
+                                   codes2(t[3], t[7]) << 6));
   }
 }
 

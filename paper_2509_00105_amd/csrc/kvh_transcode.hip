@@ -89,36 +89,50 @@ __device__ __forceinline__ float recon(float q, float scale, float mn) {
   return y;
 }
 
-// The 16 input codes of a lane, as floats.
+// The 16 input codes of a lane.  spread() lays them out one per byte (4 words), so that each code
+// then costs a single byte->float convert; the empty asm keeps the compiler from undoing that
+// into one bit-field extract plus one convert per code.
+__device__ __forceinline__ uint32_t opaque(uint32_t x) {
+  asm("" : "+v"(x));
+  return x;
+}
 template <int BITS>
 struct InCodes;
 template <>
 struct InCodes<8> {
   uintx4 w;
   __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx4>(p); }
-  __device__ __forceinline__ float get(int j) const {
-    const uint32_t v[4] = {w.x, w.y, w.z, w.w};
-    return (float)((v[j >> 2] >> (8 * (j & 3))) & 0xffu);
+  __device__ __forceinline__ float get(const uint32_t (&e)[4], int j) const { return (float)((e[j >> 2] >> (8 * (j & 3))) & 0xffu); }
+  __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
+    e[0] = w.x; e[1] = w.y; e[2] = w.z; e[3] = w.w;
   }
 };
 template <>
 struct InCodes<4> {
   uintx2 w;
   __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx2>(p); }
-  // nibbles are spread into bytes first, so that each code costs one byte->float convert
-  __device__ __forceinline__ float get(int j) const {
-    const uint32_t v = (j >> 3) ? w.y : w.x;
-    const uint32_t e = ((j & 1) ? v >> 4 : v) & 0x0f0f0f0fu;
-    return (float)((e >> (8 * ((j & 7) >> 1))) & 0xffu);
+  // e[0] / e[1] = even / odd nibbles of the first word, e[2] / e[3] of the second
+  __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
+    e[0] = opaque(w.x & 0x0f0f0f0fu);
+    e[1] = opaque((w.x >> 4) & 0x0f0f0f0fu);
+    e[2] = opaque(w.y & 0x0f0f0f0fu);
+    e[3] = opaque((w.y >> 4) & 0x0f0f0f0fu);
+  }
+  __device__ __forceinline__ float get(const uint32_t (&e)[4], int j) const {
+    return (float)((e[(j >> 3) * 2 + (j & 1)] >> (8 * ((j & 7) >> 1))) & 0xffu);
   }
 };
 template <>
 struct InCodes<2> {
   uint32_t w;
   __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint32_t>(p); }
-  __device__ __forceinline__ float get(int j) const {
-    const uint32_t e = (w >> (2 * (j & 3))) & 0x03030303u;
-    return (float)((e >> (8 * (j >> 2))) & 0xffu);
+  // e[k] holds codes k, k + 4, k + 8, k + 12 in its four bytes
+  __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) e[k] = opaque((w >> (2 * k)) & 0x03030303u);
+  }
+  __device__ __forceinline__ float get(const uint32_t (&e)[4], int j) const {
+    return (float)((e[j & 3] >> (8 * (j >> 2))) & 0xffu);
   }
 };
 
@@ -131,33 +145,29 @@ __device__ __forceinline__ uint32_t codes4(float t0, float t1, float t2, float t
   return __builtin_amdgcn_cvt_pk_u8_f32(t3, 3, a);
 }
 
-// Pack 16 positions into BITS-bit codes (channel order, LSB first) and store them.
+// Pack 16 positions into BITS-bit codes (channel order, LSB first) and store them.  The convert
+// puts a code into any byte of a word, so narrow codes are routed at that point: word i receives,
+// in its byte k, the code that belongs i fields above the bottom of output byte k, and the words
+// are then merged with one shift-or each.  (For finite positions every code is <= L, so fields
+// never overlap.)
 template <int BITS>
 __device__ __forceinline__ void store_codes16(uint8_t* p, const float (&t)[16]) {
-  uint32_t a[4];
-#pragma unroll
-  for (int k = 0; k < 4; ++k) a[k] = codes4(t[4 * k], t[4 * k + 1], t[4 * k + 2], t[4 * k + 3]);
   if constexpr (BITS == 8) {
-    uintx4 o = {a[0], a[1], a[2], a[3]};
+    uintx4 o;
+    o.x = codes4(t[0], t[1], t[2], t[3]);
+    o.y = codes4(t[4], t[5], t[6], t[7]);
+    o.z = codes4(t[8], t[9], t[10], t[11]);
+    o.w = codes4(t[12], t[13], t[14], t[15]);
     gstore_stream<uintx4>(p, o);
   } else if constexpr (BITS == 4) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      a[k] &= 0x0f0f0f0fu;  // a no-op for finite positions; keeps stray bits inside their field otherwise
-      a[k] |= a[k] >> 4;    // byte 0 = c0 | c1 << 4, byte 2 = c2 | c3 << 4
-    }
-    uintx2 o = {__builtin_amdgcn_perm(a[1], a[0], 0x06040200u), __builtin_amdgcn_perm(a[3], a[2], 0x06040200u)};
+    uintx2 o;
+    o.x = codes4(t[0], t[2], t[4], t[6]) | codes4(t[1], t[3], t[5], t[7]) << 4;
+    o.y = codes4(t[8], t[10], t[12], t[14]) | codes4(t[9], t[11], t[13], t[15]) << 4;
     gstore_stream<uintx2>(p, o);
   } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      a[k] &= 0x03030303u;
-      a[k] |= a[k] >> 6;
-      a[k] |= a[k] >> 12;  // byte 0 = c0 | c1 << 2 | c2 << 4 | c3 << 6
-    }
-    uint32_t lo = __builtin_amdgcn_perm(a[1], a[0], 0x0c0c0400u);  // bytes 0, 1
-    uint32_t hi = __builtin_amdgcn_perm(a[3], a[2], 0x04000c0cu);  // bytes 2, 3
-    gstore_stream<uint32_t>(p, lo | hi);
+    uint32_t o = codes4(t[0], t[4], t[8], t[12]) | codes4(t[1], t[5], t[9], t[13]) << 2 |
+                 codes4(t[2], t[6], t[10], t[14]) << 4 | codes4(t[3], t[7], t[11], t[15]) << 6;
+    gstore_stream<uint32_t>(p, o);
   }
 }
 
@@ -193,11 +203,13 @@ template <int DT, int BI, int BO, bool FIX, typename P>
 __device__ __forceinline__ void transcode_row(uint8_t* out, const InCodes<BI>& cw, P&& param) {
   constexpr float LI = float((1 << BI) - 1);
   float t[kTcLaneCh];
+  uint32_t e[4];
+  cw.spread(e);
 #pragma unroll
   for (int j = 0; j < kTcLaneCh; j += 2) {
     const TcParams& p0 = param(j);
     const TcParams& p1 = param(j + 1);
-    const float q0 = cw.get(j), q1 = cw.get(j + 1);
+    const float q0 = cw.get(e, j), q1 = cw.get(e, j + 1);
     const uint32_t pk = pack2<DT>(recon(q0, p0.scale, p0.mn), recon(q1, p1.scale, p1.mn));
     float x0 = t16_to_f32<DT>(pk & 0xffffu), x1 = t16_to_f32<DT>(pk >> 16);
     if constexpr (FIX) {
