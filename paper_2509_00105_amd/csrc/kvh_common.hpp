@@ -58,6 +58,21 @@ __device__ __forceinline__ uint32_t f32_to_t16(float f) {
   }
 }
 
+// ---- wave-uniform values ------------------------------------------------------------------------
+// A job descriptor fetched from memory arrives in vector registers although every lane holds the same
+// value.  Moving it to scalar registers lets row indices, bounds tests and base addresses derived from
+// it run on the scalar unit instead of costing vector instructions per row.
+__device__ __forceinline__ int32_t uniform(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint64_t uniform(uint64_t v) {
+  return (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)v) |
+         (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)(v >> 32)) << 32;
+}
+__device__ __forceinline__ int64_t uniform(int64_t v) { return (int64_t)uniform((uint64_t)v); }
+template <typename T>
+__device__ __forceinline__ T* uniform(T* p) {
+  return reinterpret_cast<T*>(uniform((uint64_t)reinterpret_cast<uintptr_t>(p)));
+}
+
 // ---- group parameters -------------------------------------------------------------------------
 // meta = mn | mx << 16 (raw 16-bit patterns as stored in the blob).
 struct GroupParams {

@@ -314,6 +314,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   } else {
     it = a.one;
   }
+  it.blob = uniform(it.blob);
+  it.n_tokens = uniform(it.n_tokens);
+  it.level = uniform(it.level);
+  it.dst_token0 = uniform(it.dst_token0);
+  it.page_table = uniform(it.page_table);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
   const int unit = blockIdx.x * kDecWaves + wave;

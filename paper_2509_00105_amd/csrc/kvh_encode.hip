@@ -119,7 +119,7 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
   for (int i = 0; i < kEncRows; ++i) {
     int t = t_first + i;
     t = t < n ? t : n - 1;
-    d[i] = gload<uintx4>(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2 + lane_src_off);
+    d[i] = gload<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
   }
   float mn[8], mx[8];
   unpack8<DT>(d[0], mn);
@@ -201,7 +201,7 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
     if (t < n) {  // wave-uniform
       float x[8];
       unpack8<DT>(d[i], x);
-      quantise_store8<BITS>(codes + (size_t)t * geo.row_bytes + lane_code_off, x, [&](int j) { return par[j]; });
+      quantise_store8<BITS>(uniform(codes + (size_t)t * geo.row_bytes) + lane_code_off, x, [&](int j) { return par[j]; });
     }
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -251,7 +251,7 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
     for (int i = 0; i < kBatch; ++i) {
       int t = t_first + i0 + i;
       t = t < n ? t : n - 1;
-      d[i] = gload<uintx4>(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2 + lane_src_off);
+      d[i] = gload<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
     }
 #pragma unroll
     for (int i = 0; i < kBatch; ++i) {
@@ -270,11 +270,11 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
       mx = row16_reduce<false>(mx);
       if (active && t < n) {
         uint32_t lo = exact_bits<DT>(mn), hi = exact_bits<DT>(mx);
-        if ((lane & 15) == 0) gstore<uint32_t>(vmeta + ((size_t)t * heads + (ch0 / kGroup)) * 4, lo | hi << 16);
+        if ((lane & 15) == 0) gstore<uint32_t>(uniform(vmeta + (size_t)t * heads * 4) + (ch0 / kGroup) * 4, lo | hi << 16);
         float2 par;
         par.x = t16_to_f32<DT>(lo);
         par.y = encode_inv<BITS>(par.x, t16_to_f32<DT>(hi));
-        quantise_store8<BITS>(codes + (size_t)t * geo.row_bytes + lane_code_off, x, [&](int) { return par; });
+        quantise_store8<BITS>(uniform(codes + (size_t)t * geo.row_bytes) + lane_code_off, x, [&](int) { return par; });
       }
     }
   }
@@ -301,6 +301,10 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   } else {
     it = a.one;
   }
+  it.blob = uniform(it.blob);
+  it.src_token0 = uniform(it.src_token0);
+  it.n_tokens = uniform(it.n_tokens);
+  it.level = uniform(it.level);
   const int split = a.items != nullptr ? kNoSplit : a.split;  // batch items are never token-dropped entries
   const int64_t jump = a.items != nullptr ? 0 : a.jump;
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;

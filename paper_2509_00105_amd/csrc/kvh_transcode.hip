@@ -427,6 +427,11 @@ __global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(Transc
   } else {
     it = a.one;
   }
+  it.src = uniform(it.src);
+  it.dst = uniform(it.dst);
+  it.n_tokens = uniform(it.n_tokens);
+  it.level_in = uniform(it.level_in);
+  it.level_out = uniform(it.level_out);
   const int nspans = (a.c + kTcSpanCh - 1) / kTcSpanCh;
   const int g = blockIdx.x / nspans;
   const int span = blockIdx.x - g * nspans;
