@@ -9,7 +9,7 @@
 //   V (statistics over the 128 channels of a head): a head is 16 lanes x 8 channels, reduced
 //     with a 4-step rotate-and-combine inside the 16-lane DPP row.
 // Quantised codes are produced with the packed float->u8 convert, which rounds to nearest even
-// and inserts the byte in one instruction; narrower codes are then squeezed out of the bytes.
+// and inserts the byte in one instruction; narrow codes are routed to their byte at that point.
 #include "kvh_common.hpp"
 
 namespace kvh {
@@ -268,13 +268,17 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
       mx = __builtin_fmaxf(mx, x[7]);
       mn = row16_reduce<true>(mn);
       mx = row16_reduce<false>(mx);
-      if (active && t < n) {
-        uint32_t lo = exact_bits<DT>(mn), hi = exact_bits<DT>(mx);
-        if ((lane & 15) == 0) gstore<uint32_t>(uniform(vmeta + (size_t)t * heads * 4) + (ch0 / kGroup) * 4, lo | hi << 16);
-        float2 par;
-        par.x = t16_to_f32<DT>(lo);
-        par.y = encode_inv<BITS>(par.x, t16_to_f32<DT>(hi));
-        quantise_store8<BITS>(uniform(codes + (size_t)t * geo.row_bytes) + lane_code_off, x, [&](int) { return par; });
+      if (t < n) {  // wave-uniform; the row addresses are formed on the scalar unit, outside the per-lane test
+        uint8_t* meta_row = uniform(vmeta + (size_t)t * heads * 4);
+        uint8_t* code_row = uniform(codes + (size_t)t * geo.row_bytes);
+        if (active) {
+          uint32_t lo = exact_bits<DT>(mn), hi = exact_bits<DT>(mx);
+          if ((lane & 15) == 0) gstore<uint32_t>(meta_row + (ch0 / kGroup) * 4, lo | hi << 16);
+          float2 par;
+          par.x = t16_to_f32<DT>(lo);
+          par.y = encode_inv<BITS>(par.x, t16_to_f32<DT>(hi));
+          quantise_store8<BITS>(code_row + lane_code_off, x, [&](int) { return par; });
+        }
       }
     }
   }
