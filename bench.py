@@ -29,8 +29,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # same command (profiles/codec_kernels_llama3_8b_8k_bf16.md): (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB, the
 # factors being what the counters read for the plain copy kernel of known size.  Re-measure after kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    ("encode", 8): 1651606528, ("encode", 4): 1367870464, ("encode", 2): 1249452032,
-    ("decode", 8): 1637568512, ("decode", 4): 1369637888, ("decode", 2): 1235354624,
+    ("encode", 8): 1665816576, ("encode", 4): 1434494976, ("encode", 2): 1263828992,
+    ("decode", 8): 1637622784, ("decode", 4): 1369648128, ("decode", 2): 1235448832,
+    ("transcode", 8, 4): 850662400, ("transcode", 8, 2): 717379584, ("transcode", 4, 2): 449307648,
 }
 
 
@@ -236,6 +237,7 @@ def main():
         moved = blobs[a].numel() + tc_out[(a, b)].numel()
         transcode.append({"kernel": "transcode_kernel", "bits_in": ba, "bits_out": bb, "avg_ms": avg, "min_ms": min(durs),
                           "algorithmic_bytes": moved, "hbm_frac": moved / avg / 1e6 / HBM_PEAK_GBPS,
+                          "traffic": MEASURED_TRAFFIC_BYTES.get(("transcode", ba, bb)) if args.workload == "llama3_8b_8k" else None,
                           "elements_per_s": 2 * l * N * c / avg * 1e3,
                           "unfused_ms": by_op[("decode", ba)] + by_op[("encode", bb)]})
     dec2 = [r for r in per_kernel if r["op"] == "decode"]
