@@ -202,6 +202,39 @@ typedef struct {
 int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
                         int32_t* status_dev, void* stream);
 
+/* ---- Load path ------------------------------------------------------------------------------------
+ * A stored entry costs size / Bandwidth of loading delay before it can be reused, plus its decompression
+ * (the paper's utility charges the first, its estimator profiles the second; Design section).  The loader
+ * moves blobs that sit in PINNED host memory (the DRAM tier) through a ring of device staging slots and
+ * decodes them, so that the copy of blob i + 1 overlaps the decode of blob i.  It is a host-side object: one
+ * copy stream (default priority) and two events per slot; the staging buffer is the caller's device memory.
+ * Not thread-safe; one loader serves one device (the one current at creation). */
+typedef struct kvh_loader kvh_loader;
+
+/* One blob to load.  HOST array, host struct. */
+typedef struct {
+  const void* blob_host;     /* pinned host memory holding kvh_blob_size(l, n_tokens, c, level) bytes */
+  int32_t n_tokens;          /* tokens in the blob */
+  int32_t level;             /* level it was stored at */
+  int64_t dst_token0;        /* logical position of its first token in the destination */
+  const int32_t* page_table; /* DEVICE pointer to the request's table, or NULL for contiguous */
+} kvh_load_item;
+
+/* Create a loader over `staging_dev` (device memory, 16-byte aligned, staging_bytes long), cut into n_slots
+ * equal slots (1..64; 2 = double buffering).  Each slot must hold the largest blob that will be loaded. */
+int kvh_loader_create(kvh_loader** out, void* staging_dev, size_t staging_bytes, int n_slots);
+/* Bytes per slot (0 for NULL). */
+size_t kvh_loader_slot_bytes(const kvh_loader* loader);
+/* Enqueue, for every item in order: wait until the slot is free, copy the blob host -> slot on the loader's
+ * copy stream, then decode it on `stream` into `dst` (contiguous or paged, as kvh_decode).  Returns once
+ * everything is enqueued; results are valid after `stream` has been synchronised; host blobs and the
+ * staging buffer must stay alive until then.  status_dev, if not NULL, has one zeroed int32 per item
+ * (KVH_DEV_HEADER_MISMATCH as for kvh_decode_batch).  All items are validated before anything is enqueued. */
+int kvh_loader_run(kvh_loader* loader, const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c,
+                   const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
+/* Wait for the loader's copies, then release its stream and events (not the staging buffer). */
+int kvh_loader_destroy(kvh_loader* loader);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
  * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that
  * scales the HBM byte counters and as the practical copy-bandwidth ceiling of the device. */

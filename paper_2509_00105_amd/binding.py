@@ -31,7 +31,9 @@ DEC_ITEM = np.dtype([("blob", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("d
                      ("page_table", "<u8")], align=True)
 TC_ITEM = np.dtype([("src", "<u8"), ("dst", "<u8"), ("n_tokens", "<i4"), ("level_in", "<i4"), ("level_out", "<i4"),
                     ("reserved", "<i4")], align=True)
-assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32
+LOAD_ITEM = np.dtype([("blob_host", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"),
+                      ("page_table", "<u8")], align=True)  # a HOST array, unlike the three above
+assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32 and LOAD_ITEM.itemsize == 32
 
 _lib = None
 
@@ -73,6 +75,14 @@ def lib() -> ctypes.CDLL:
         L.kvh_transcode.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp]
         L.kvh_transcode_batch.restype = i32
         L.kvh_transcode_batch.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+        L.kvh_loader_create.restype = i32
+        L.kvh_loader_create.argtypes = [ctypes.POINTER(vp), vp, sz, i32]
+        L.kvh_loader_slot_bytes.restype = sz
+        L.kvh_loader_slot_bytes.argtypes = [vp]
+        L.kvh_loader_run.restype = i32
+        L.kvh_loader_run.argtypes = [vp, vp, i32, i32, i32, i32, view, i32, vp, vp]
+        L.kvh_loader_destroy.restype = i32
+        L.kvh_loader_destroy.argtypes = [vp]
         L.kvh_copy_probe.restype = i32
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_strerror.restype = ctypes.c_char_p
@@ -299,6 +309,63 @@ def transcode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int,
     _check(lib().kvh_transcode_batch(items.data_ptr(), n_items, max_tokens_per_item, _dt_code(dtype), l, c,
                                      status.data_ptr() if status is not None else None, _stream_ptr(stream)),
            "kvh_transcode_batch")
+
+
+class Loader:
+    """kvh_loader_*: blobs in pinned host memory -> staging slots in `staging` (uint8 device tensor) -> decode."""
+
+    def __init__(self, staging: torch.Tensor, n_slots: int = 2):
+        _require_cuda(staging)
+        if staging.dtype != torch.uint8 or not staging.is_contiguous():
+            raise ValueError("staging must be a contiguous uint8 device tensor")
+        self._staging = staging  # keeps the buffer alive as long as the loader
+        self._h = ctypes.c_void_p()
+        _check(lib().kvh_loader_create(ctypes.byref(self._h), staging.data_ptr(), staging.numel(), n_slots),
+               "kvh_loader_create")
+        self._keep = None
+
+    @property
+    def slot_bytes(self) -> int:
+        return lib().kvh_loader_slot_bytes(self._h)
+
+    def run(self, host_blobs, n_tokens, levels, dst_token0, k_dst: torch.Tensor, v_dst: torch.Tensor,
+            page_tables=None, block_tokens: int = 16, status: torch.Tensor | None = None, stream=None) -> None:
+        """kvh_loader_run over pinned uint8 host tensors `host_blobs`; page_tables: int32 device tensors or None."""
+        paged = page_tables is not None
+        view, dt = _view(k_dst, v_dst, paged)
+        _require_cuda(status)
+        n = len(host_blobs)
+        for b in host_blobs:
+            if b.is_cuda or not b.is_pinned() or b.dtype != torch.uint8:
+                raise ValueError("host blobs must be pinned uint8 host tensors")
+        if status is not None and (status.dtype != torch.int32 or status.numel() < n):
+            raise ValueError("status must be int32 with one entry per item")
+        a = np.zeros(n, dtype=LOAD_ITEM)
+        a["blob_host"] = [b.data_ptr() for b in host_blobs]
+        a["n_tokens"], a["level"], a["dst_token0"] = n_tokens, levels, dst_token0
+        if paged:
+            for t in page_tables:
+                _require_cuda(t)
+                if t.dtype != torch.int32:
+                    raise ValueError("page tables must be int32")
+            a["page_table"] = [t.data_ptr() for t in page_tables]
+        l, c = k_dst.shape[0], k_dst.shape[-1]
+        self._keep = (host_blobs, page_tables)  # the copies are asynchronous: keep the sources alive
+        _check(lib().kvh_loader_run(self._h, a.ctypes.data, n, dt, l, c, ctypes.byref(view), block_tokens,
+                                    status.data_ptr() if status is not None else None, _stream_ptr(stream)),
+               "kvh_loader_run")
+
+    def close(self) -> None:
+        if self._h:
+            h, self._h = self._h, ctypes.c_void_p()
+            _check(lib().kvh_loader_destroy(h), "kvh_loader_destroy")
+        self._keep = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -35,7 +35,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
     assert set(names) >= {"kvh_encode", "kvh_decode", "kvh_encode_batch", "kvh_decode_batch", "kvh_encode_chunked",
                           "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe",
-                          "kvh_kept_tokens", "kvh_encode_kept", "kvh_decode_kept", "kvh_transcode", "kvh_transcode_batch"}
+                          "kvh_kept_tokens", "kvh_encode_kept", "kvh_decode_kept", "kvh_transcode", "kvh_transcode_batch",
+                          "kvh_loader_create", "kvh_loader_run", "kvh_loader_destroy", "kvh_loader_slot_bytes"}
     for n in names:
         assert hasattr(lib, n), n
 
@@ -141,6 +142,16 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.kvh_transcode_batch(None, 1, 256, 0, 1, 1024, None, None) == E_ARG
     assert lib.kvh_transcode_batch(P, 0, 256, 0, 1, 1024, None, None) == E_ARG
     assert lib.kvh_transcode_batch(P, 1, 256, 0, 1, 1000, None, None) == E_SHAPE
+    h = ctypes.c_void_p()
+    assert lib.kvh_loader_create(None, P, 1 << 20, 2) == E_ARG
+    assert lib.kvh_loader_create(ctypes.byref(h), None, 1 << 20, 2) == E_ARG and not h
+    assert lib.kvh_loader_create(ctypes.byref(h), P, 1 << 20, 0) == E_ARG
+    assert lib.kvh_loader_create(ctypes.byref(h), P, 1 << 20, 65) == E_ARG
+    assert lib.kvh_loader_create(ctypes.byref(h), P + 8, 1 << 20, 2) == E_ALIGN
+    assert lib.kvh_loader_create(ctypes.byref(h), P, 100, 2) == E_SIZE and not h
+    assert lib.kvh_loader_run(None, P, 1, 0, 1, 1024, v, 16, None, None) == E_ARG
+    assert lib.kvh_loader_destroy(None) == E_ARG
+    assert lib.kvh_loader_slot_bytes(None) == 0
     assert lib.kvh_copy_probe(P, P + 4096, 100, None) == E_ALIGN
     assert lib.kvh_copy_probe(None, P, 4096, None) == E_ARG
 

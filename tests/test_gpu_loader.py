@@ -1,0 +1,120 @@
+"""GPU parity of the load path (kvh_loader_*): blobs in pinned host memory, copied through a ring of device
+staging slots and decoded, against the CPU oracle's decode of the same blobs.  Bar: reconstructed values as raw
+16-bit patterns, bit for bit.  Blobs are the ORACLE's."""
+import numpy as np
+import pytest
+
+import kv_inputs as gen
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = gen.F16, gen.BF16
+TDT = {F16: torch.float16, BF16: torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def kvh():
+    import paper_2509_00105_amd as m
+
+    m.lib()
+    return m
+
+
+def to_host(t) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def make_entries(dt, l, c, lens, levels, seed):
+    """Oracle blobs (pinned) of consecutive pieces of one context, and the oracle's decode of the whole."""
+    N = sum(lens)
+    k, v = gen.make_kv(l, N, c, dt, seed=seed)
+    blobs, want_k, want_v, t0s = [], np.zeros_like(k), np.zeros_like(v), []
+    t0 = 0
+    for n, lv in zip(lens, levels):
+        b = oracle.encode(np.ascontiguousarray(k[:, t0:t0 + n]), np.ascontiguousarray(v[:, t0:t0 + n]), dt, lv)
+        dk, dv = oracle.decode(b, dt, l, n, c, lv)
+        want_k[:, t0:t0 + n], want_v[:, t0:t0 + n] = dk, dv
+        blobs.append(torch.from_numpy(b).pin_memory())
+        t0s.append(t0)
+        t0 += n
+    return blobs, t0s, want_k, want_v, N
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("n_slots", [1, 2, 3])
+def test_pipelined_load_matches_oracle(kvh, n_slots, dt):
+    l, c = 2, 256
+    lens = [256, 130, 256, 1, 384, 77, 256]
+    levels = [0, 2, 1, 0, 2, 1, 2]
+    blobs, t0s, want_k, want_v, N = make_entries(dt, l, c, lens, levels, seed=60 + n_slots)
+    slot = max(b.numel() for b in blobs)
+    staging = torch.empty(n_slots * slot + 16, dtype=torch.uint8, device="cuda")
+    ld = kvh.Loader(staging, n_slots)
+    assert ld.slot_bytes >= slot
+    ok = torch.full((l, N, c), 3.0, dtype=TDT[dt], device="cuda"); ov = torch.full_like(ok, 3.0)
+    status = torch.zeros(len(lens), dtype=torch.int32, device="cuda")
+    ld.run(blobs, lens, levels, t0s, ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0] * len(lens)
+    assert np.array_equal(to_host(ok), want_k) and np.array_equal(to_host(ov), want_v)
+    # a second run on the same loader (slots are reused across runs), in reverse order, into a fresh destination
+    ok2 = torch.zeros_like(ok); ov2 = torch.zeros_like(ov)
+    ld.run(blobs[::-1], lens[::-1], levels[::-1], t0s[::-1], ok2, ov2, status=status)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(ok2), want_k) and np.array_equal(to_host(ov2), want_v)
+    ld.close()
+
+
+def test_pipelined_load_paged_and_header_mismatch(kvh):
+    dt, l, c, bt = BF16, 2, 128, 16
+    lens, levels = [64, 48, 80], [1, 0, 2]
+    blobs, t0s, want_k, want_v, N = make_entries(dt, l, c, lens, levels, seed=70)
+    P = N // bt
+    table = np.random.default_rng(1).permutation(P + 3).astype(np.int32)[:P]
+    pk = np.zeros((l, P + 3, bt, c), np.uint16); pv = np.zeros_like(pk)
+    for lv, b, n, t0 in zip(levels, blobs, lens, t0s):
+        assert oracle.decode_into(b.numpy(), dt, l, n, c, lv, pk, pv, dst_token0=t0, page_table=table, block_tokens=bt) == 0
+    gk = torch.zeros((l, P + 3, bt, c), dtype=torch.bfloat16, device="cuda"); gv = torch.zeros_like(gk)
+    tab = torch.from_numpy(table).cuda()
+    staging = torch.empty(2 * max(b.numel() for b in blobs), dtype=torch.uint8, device="cuda")
+    ld = kvh.Loader(staging, 2)
+    status = torch.zeros(3, dtype=torch.int32, device="cuda")
+    ld.run(blobs, lens, levels, t0s, gk, gv, page_tables=[tab] * 3, block_tokens=bt, status=status)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0, 0]
+    assert np.array_equal(to_host(gk), pk) and np.array_equal(to_host(gv), pv)
+    # item 1 claims the wrong level: it alone reports a mismatch and writes nothing
+    gk.zero_(); gv.zero_(); status.zero_()
+    wrong = list(levels); wrong[1] = 1
+    bigger = [blobs[0], torch.cat([blobs[1], torch.zeros(16, dtype=torch.uint8)]).pin_memory(), blobs[2]]
+    ld.run(bigger, lens, wrong, t0s, gk, gv, page_tables=[tab] * 3, block_tokens=bt, status=status)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 1, 0]
+    exp_k = pk.copy(); exp_v = pv.copy()
+    for s in range(t0s[1], t0s[1] + lens[1]):
+        exp_k[:, table[s // bt], s % bt] = 0; exp_v[:, table[s // bt], s % bt] = 0
+    assert np.array_equal(to_host(gk), exp_k) and np.array_equal(to_host(gv), exp_v)
+    ld.close()
+
+
+def test_loader_argument_errors(kvh):
+    staging = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kvh.KVHError):
+        kvh.Loader(staging, 0)
+    with pytest.raises(kvh.KVHError):
+        kvh.Loader(staging, 65)
+    with pytest.raises(kvh.KVHError):
+        kvh.Loader(staging[:32], 2)  # slots smaller than a header
+    ld = kvh.Loader(staging, 2)
+    k = torch.zeros((1, 256, 128), dtype=torch.float16, device="cuda")
+    big = torch.zeros(kvh.blob_size(1, 256, 128, 0), dtype=torch.uint8).pin_memory()
+    with pytest.raises(kvh.KVHError):  # a 67,648-byte blob does not fit a 32 KiB slot
+        ld.run([big], [256], [0], [0], k, k.clone())
+    with pytest.raises(kvh.KVHError):
+        ld.run([big], [256], [5], [0], k, k.clone())
+    with pytest.raises(ValueError):  # pageable host memory is refused by the binding
+        ld.run([torch.zeros(100, dtype=torch.uint8)], [1], [0], [0], k, k.clone())
+    ld.close()
+    torch.cuda.synchronize()
