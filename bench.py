@@ -212,6 +212,65 @@ def main():
                 tev[r][j + 1].record(stream)
         torch.cuda.synchronize()
     assert all(int(tc_status[pr].abs().sum().item()) == 0 for pr in tc_pairs), "a transcode reported a header mismatch"
+
+    # Also outside the timed region: the load path.  The same 32 blobs per level sit in pinned host memory (the
+    # DRAM tier); `pipelined` = kvh_loader_run with 2 staging slots (copy of group g+1 overlaps decode of group g),
+    # `serial` = one copy of all blobs, then decode_batch; `uncompressed` = copying the 16-bit KV itself.  These
+    # are the PCIe-inclusive figures of the path; they are not part of `value`.
+    load_path = []
+    with torch.cuda.stream(stream):
+        host_unc = torch.empty(kv.numel() * 2, dtype=torch.uint8).pin_memory()
+        host_unc.copy_(kv.view(torch.uint8).reshape(-1), non_blocking=False)
+        le = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        out.view(torch.uint8).reshape(-1).copy_(host_unc, non_blocking=True)  # warm-up
+        le[0].record(stream)
+        for _ in range(3):
+            out.view(torch.uint8).reshape(-1).copy_(host_unc, non_blocking=True)
+        le[1].record(stream)
+        torch.cuda.synchronize()
+        unc_ms = le[0].elapsed_time(le[1]) / 3
+        load_path.append({"mode": "uncompressed", "bits": 16, "ms": unc_ms, "pcie_GBps": host_unc.numel() / unc_ms / 1e6,
+                          "uncompressed_GBps": host_unc.numel() / unc_ms / 1e6})
+        del host_unc
+        n_slots = 2  # double buffering; a slot takes 4 chunks at 8 bits, 7 at 4 bits, 14 at 2 bits
+        staging = torch.empty(n_slots * (4 * kvh.blob_size(l, chunk, c, 0) + 1024), dtype=torch.uint8, device=dev)
+        loader = kvh.Loader(staging, n_slots)
+        for level in range(3):
+            size = kvh.blob_size(l, chunk, c, level)
+            host_all = torch.empty(n_chunks * size, dtype=torch.uint8).pin_memory()
+            host_all.copy_(blobs[level], non_blocking=False)
+            host_blobs = [host_all[i * size:(i + 1) * size] for i in range(n_chunks)]
+            dev_all = torch.empty_like(blobs[level])
+            ptrs = [dev_all.data_ptr() + i * size for i in range(n_chunks)]
+            items = kvh.make_dec_items(ptrs, [chunk] * n_chunks, [level] * n_chunks, [i * chunk for i in range(n_chunks)],
+                                       [0] * n_chunks, dev)
+            status[level].zero_()
+
+            def pipelined():
+                loader.run(host_blobs, [chunk] * n_chunks, [level] * n_chunks, [i * chunk for i in range(n_chunks)],
+                           out[0], out[1], status=status[level], stream=stream)
+
+            def serial():
+                dev_all.copy_(host_all, non_blocking=True)
+                kvh.decode_batch(items, n_chunks, chunk, out[0], out[1], status=status[level], stream=stream)
+
+            for mode, fn in (("pipelined", pipelined), ("serial", serial)):
+                fn()
+                torch.cuda.synchronize()
+                le = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                le[0].record(stream)
+                for _ in range(3):
+                    fn()
+                le[1].record(stream)
+                torch.cuda.synchronize()
+                ms = le[0].elapsed_time(le[1]) / 3
+                load_path.append({"mode": mode, "bits": kvh.level_bits(level), "ms": ms,
+                                  "pcie_GBps": n_chunks * size / ms / 1e6,
+                                  "uncompressed_GBps": 2 * l * N * c * 2 / ms / 1e6})
+            assert int(status[level].abs().sum().item()) == 0
+            del host_all, host_blobs, dev_all
+        loader.close()
+        del staging
     step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
@@ -261,6 +320,7 @@ def main():
         "copy_probe_GBps": copy_gbps,
         "token_dropping": dropping,
         "transcode": transcode,
+        "load_path": load_path,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),
     }

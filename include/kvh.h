@@ -206,14 +206,17 @@ int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_token
  * A stored entry costs size / Bandwidth of loading delay before it can be reused, plus its decompression
  * (the paper's utility charges the first, its estimator profiles the second; Design section).  The loader
  * moves blobs that sit in PINNED host memory (the DRAM tier) through a ring of device staging slots and
- * decodes them, so that the copy of blob i + 1 overlaps the decode of blob i.  It is a host-side object: one
- * copy stream (default priority) and two events per slot; the staging buffer is the caller's device memory.
- * Not thread-safe; one loader serves one device (the one current at creation). */
+ * decodes them.  Consecutive blobs are packed into groups that fill a slot; a group is moved by one launch
+ * of a copy kernel that reads the host memory in place, then decoded by one batched decode launch, so the
+ * copy of group g + 1 overlaps the decode of group g.  It is a host-side object: one copy stream (default
+ * priority) and two events per slot; the staging buffer is the caller's device memory.  Not thread-safe; one
+ * loader serves one device (the one current at creation). */
 typedef struct kvh_loader kvh_loader;
 
 /* One blob to load.  HOST array, host struct. */
 typedef struct {
-  const void* blob_host;     /* pinned host memory holding kvh_blob_size(l, n_tokens, c, level) bytes */
+  const void* blob_host;     /* pinned (device-visible) host memory, 16-byte aligned, holding
+                                kvh_blob_size(l, n_tokens, c, level) bytes; ordinary pageable memory is refused */
   int32_t n_tokens;          /* tokens in the blob */
   int32_t level;             /* level it was stored at */
   int64_t dst_token0;        /* logical position of its first token in the destination */
@@ -221,15 +224,17 @@ typedef struct {
 } kvh_load_item;
 
 /* Create a loader over `staging_dev` (device memory, 16-byte aligned, staging_bytes long), cut into n_slots
- * equal slots (1..64; 2 = double buffering).  Each slot must hold the largest blob that will be loaded. */
+ * equal slots (1..64; 2 = double buffering).  The first 1 KiB of a slot holds descriptors; the rest
+ * (kvh_loader_slot_bytes) must hold the largest blob that will be loaded and is best sized for several. */
 int kvh_loader_create(kvh_loader** out, void* staging_dev, size_t staging_bytes, int n_slots);
-/* Bytes per slot (0 for NULL). */
+/* Bytes a slot offers to blobs (0 for NULL). */
 size_t kvh_loader_slot_bytes(const kvh_loader* loader);
-/* Enqueue, for every item in order: wait until the slot is free, copy the blob host -> slot on the loader's
- * copy stream, then decode it on `stream` into `dst` (contiguous or paged, as kvh_decode).  Returns once
- * everything is enqueued; results are valid after `stream` has been synchronised; host blobs and the
- * staging buffer must stay alive until then.  status_dev, if not NULL, has one zeroed int32 per item
- * (KVH_DEV_HEADER_MISMATCH as for kvh_decode_batch).  All items are validated before anything is enqueued. */
+/* Enqueue, group by group in item order: wait until the next slot is free, copy the group's blobs host ->
+ * slot on the loader's copy stream, then decode them on `stream` into `dst` (contiguous or paged, as
+ * kvh_decode_batch; token-dropped blobs are not accepted).  Returns once everything is enqueued; results
+ * are valid after `stream` has been synchronised; host blobs and the staging buffer must stay alive until
+ * then.  status_dev, if not NULL, has one zeroed int32 per item (KVH_DEV_HEADER_MISMATCH as for
+ * kvh_decode_batch).  All items are validated before anything is enqueued. */
 int kvh_loader_run(kvh_loader* loader, const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c,
                    const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
 /* Wait for the loader's copies, then release its stream and events (not the staging buffer). */

@@ -50,9 +50,10 @@ def test_pipelined_load_matches_oracle(kvh, n_slots, dt):
     levels = [0, 2, 1, 0, 2, 1, 2]
     blobs, t0s, want_k, want_v, N = make_entries(dt, l, c, lens, levels, seed=60 + n_slots)
     slot = max(b.numel() for b in blobs)
-    staging = torch.empty(n_slots * slot + 16, dtype=torch.uint8, device="cuda")
+    # slots that hold the largest blob plus the descriptor area: groups of one to a few blobs, several ring turns
+    staging = torch.empty(n_slots * (slot + 1024), dtype=torch.uint8, device="cuda")
     ld = kvh.Loader(staging, n_slots)
-    assert ld.slot_bytes >= slot
+    assert slot <= ld.slot_bytes < slot + 1024
     ok = torch.full((l, N, c), 3.0, dtype=TDT[dt], device="cuda"); ov = torch.full_like(ok, 3.0)
     status = torch.zeros(len(lens), dtype=torch.int32, device="cuda")
     ld.run(blobs, lens, levels, t0s, ok, ov, status=status)
@@ -78,7 +79,7 @@ def test_pipelined_load_paged_and_header_mismatch(kvh):
         assert oracle.decode_into(b.numpy(), dt, l, n, c, lv, pk, pv, dst_token0=t0, page_table=table, block_tokens=bt) == 0
     gk = torch.zeros((l, P + 3, bt, c), dtype=torch.bfloat16, device="cuda"); gv = torch.zeros_like(gk)
     tab = torch.from_numpy(table).cuda()
-    staging = torch.empty(2 * max(b.numel() for b in blobs), dtype=torch.uint8, device="cuda")
+    staging = torch.empty(2 * (max(b.numel() for b in blobs) + 1024), dtype=torch.uint8, device="cuda")
     ld = kvh.Loader(staging, 2)
     status = torch.zeros(3, dtype=torch.int32, device="cuda")
     ld.run(blobs, lens, levels, t0s, gk, gv, page_tables=[tab] * 3, block_tokens=bt, status=status)
@@ -116,5 +117,13 @@ def test_loader_argument_errors(kvh):
         ld.run([big], [256], [5], [0], k, k.clone())
     with pytest.raises(ValueError):  # pageable host memory is refused by the binding
         ld.run([torch.zeros(100, dtype=torch.uint8)], [1], [0], [0], k, k.clone())
+    # ... and by the library itself (the copy kernel would read it in place)
+    import ctypes
+    from paper_2509_00105_amd.binding import LOAD_ITEM, _KVView
+    pageable = np.zeros(kvh.blob_size(1, 1, 128, 0) + 16, dtype=np.uint8)
+    a = np.zeros(1, dtype=LOAD_ITEM)
+    a["blob_host"], a["n_tokens"] = (pageable.ctypes.data + 15) & ~15, 1
+    view = _KVView(k.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1))
+    assert kvh.lib().kvh_loader_run(ld._h, a.ctypes.data, 1, 0, 1, 128, ctypes.byref(view), 16, None, None) == -1
     ld.close()
     torch.cuda.synchronize()
