@@ -271,6 +271,46 @@ def main():
             del host_all, host_blobs, dev_all
         loader.close()
         del staging
+
+    # Host only, outside the timed region: the storage policy on a synthetic population shaped like the paper's
+    # set-up (100 GB of DRAM, 400 GB of SSD at 1 GB/s; DRAM bandwidth = the PCIe rate measured above).  Entries:
+    # lognormal lengths as in the mixed-batch workload, Zipf frequencies, choices = 16-bit KV and the three levels
+    # (sizes from kvh_blob_size), quality = 1 - sensitivity_i * loss(bits) with a made-up loss table (the paper's
+    # curves need its datasets).  6,000 entries are about 3 TB of 16-bit KV against 0.5 TB of storage.  Reported:
+    # planner time and what it decided.
+    prng = np.random.default_rng(cfg.seed)
+    n_entries = 6_000
+    lengths = np.clip(np.exp(prng.normal(np.log(4096) - 0.32, 0.8, n_entries)), 256, 32768).astype(np.int64) // 256 * 256
+    freqs = 1.0 / (1.0 + prng.permutation(n_entries)) ** 0.8
+    sens = np.clip(prng.lognormal(0.0, 0.75, n_entries), 0.0, 3.5)
+    loss = {16: 0.0, 8: 0.002, 4: 0.03, 2: 0.25}
+    per_chunk = [2 * l * chunk * c * 2] + [kvh.blob_size(l, chunk, c, lv) for lv in range(3)]
+    sizes_p = [[float(pc * (n // chunk)) for pc in per_chunk] for n in lengths]
+    quals_p = [[1.0 - s_ * loss[b] for b in (16, 8, 4, 2)] for s_ in sens]
+    tiers_p = [(load_path[0]["pcie_GBps"] * 1e9, 100e9), (1e9, 400e9)]
+    alpha_p = 2.0  # seconds of delay one unit of quality is worth
+    tp0 = time.perf_counter()
+    p_tier, p_choice, p_total = kvh.policy_plan(freqs, sizes_p, quals_p, alpha_p, tiers_p)
+    tp1 = time.perf_counter()
+    tk0 = time.perf_counter()
+    ent_c = np.zeros(n_entries, dtype=kvh.binding.POLICY_ENTRY)
+    ent_c["freq"], ent_c["n_choices"], ent_c["first"] = freqs, 4, np.arange(n_entries) * 4
+    flat_s, flat_q = np.ascontiguousarray(sizes_p, dtype=np.float64).reshape(-1), np.ascontiguousarray(quals_p, dtype=np.float64).reshape(-1)
+    tr_c = np.zeros(2, dtype=kvh.binding.POLICY_TIER)
+    tr_c["bandwidth"], tr_c["capacity"] = [t[0] for t in tiers_p], [t[1] for t in tiers_p]
+    to_c, co_c = np.empty(n_entries, np.int32), np.empty(n_entries, np.int32)
+    tk1 = time.perf_counter()
+    rc = kvh.lib().kvh_policy_plan(ent_c.ctypes.data, n_entries, flat_s.ctypes.data, flat_q.ctypes.data, 4 * n_entries,
+                                   tr_c.ctypes.data, 2, alpha_p, to_c.ctypes.data, co_c.ctypes.data, None)
+    tk2 = time.perf_counter()
+    assert rc == 0 and (co_c == p_choice).all()
+    policy = {"entries": n_entries, "choices_per_entry": 4, "tiers": [{"bandwidth_GBps": t[0] / 1e9, "capacity_GB": t[1] / 1e9} for t in tiers_p],
+              "full_size_GB": float(sum(s_[0] for s_ in sizes_p)) / 1e9, "alpha": alpha_p,
+              "native_plan_ms": (tk2 - tk1) * 1e3, "entries_per_s": n_entries / (tk2 - tk1),
+              "with_python_marshalling_ms": (tp1 - tp0) * 1e3, "total_utility": p_total,
+              "placed": {"tier%d" % t: {str(b): int(((p_tier == t) & (p_choice == j)).sum()) for j, b in enumerate((16, 8, 4, 2))}
+                         for t in range(2)},
+              "evicted": int((p_tier < 0).sum())}
     step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
@@ -321,6 +361,7 @@ def main():
         "token_dropping": dropping,
         "transcode": transcode,
         "load_path": load_path,
+        "policy": policy,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),
     }

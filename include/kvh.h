@@ -240,6 +240,41 @@ int kvh_loader_run(kvh_loader* loader, const kvh_load_item* items, int n_items, 
 /* Wait for the loader's copies, then release its stream and events (not the staging buffer). */
 int kvh_loader_destroy(kvh_loader* loader);
 
+/* ---- Storage policy (host only; no device work) -------------------------------------------------------
+ * The paper's policy optimizer (Design section): Utility(i) = Freq(i) * (alpha * Quality(i, M_i, R_i) -
+ * size(i, M_i, R_i) / Bandwidth); the marginal utility drop of going from rate m to rate n is
+ * (Utility(i, m) - Utility(i, n)) / (bytes the step frees); per storage tier the choice (evict, store in
+ * full quality, compress) with the minimal marginal utility drop is taken greedily until the tier holds what
+ * is left.  Readings: the utility's missing parenthesis closes after the fraction; eviction has size 0 and
+ * utility 0; an entry starts at its best allowed choice; a step may go to any smaller choice (this walks the
+ * upper convex hull and reaches the linear-relaxation optimum up to one fractional step); what a tier evicts
+ * is offered to the next tier with that tier's bandwidth.  Quality values come from the caller (the paper's
+ * estimator builds them from datasets; none are shipped here). */
+typedef struct {
+  double freq;        /* estimated future hit frequency, >= 0 */
+  int32_t first;      /* index of the entry's first choice in `sizes` / `qualities` */
+  int32_t n_choices;  /* >= 1; choices ordered by strictly decreasing size, choice 0 = full quality */
+  int32_t min_choice; /* 0 for a new entry; for a stored entry the choice it is held at (it cannot regain quality) */
+  int32_t reserved;   /* 0 */
+} kvh_policy_entry;
+
+typedef struct {
+  double bandwidth; /* bytes per second from this tier to the GPU, > 0 */
+  double capacity;  /* bytes, >= 0 (may be +inf) */
+} kvh_policy_tier;
+
+double kvh_policy_utility(double freq, double alpha, double quality, double size_bytes, double bandwidth);
+double kvh_policy_marginal_utility_drop(double u_m, double u_n, double size_m, double size_n);
+
+/* Plan all entries over the tiers (tier 0 first).  sizes[] are whole numbers of bytes (e.g. kvh_blob_size);
+ * tier_out[i] = tier index or -1 (evicted everywhere), choice_out[i] = chosen choice or -1; *total_utility_out
+ * (nullable) = sum of the utilities of the placed entries in index order.  Host arrays throughout.
+ * Errors: KVH_E_ARG (null pointer, counts < 1, non-finite or negative values, sizes not whole or not strictly
+ * decreasing), KVH_E_SHAPE (an entry's choice range or min_choice out of bounds). */
+int kvh_policy_plan(const kvh_policy_entry* entries, int n_entries, const double* sizes, const double* qualities,
+                    int n_choices_total, const kvh_policy_tier* tiers, int n_tiers, double alpha, int32_t* tier_out,
+                    int32_t* choice_out, double* total_utility_out);
+
 /* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
  * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that
  * scales the HBM byte counters and as the practical copy-bandwidth ceiling of the device. */

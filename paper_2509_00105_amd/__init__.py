@@ -8,5 +8,5 @@ importing the binding without a built library raises.
 from .binding import (  # noqa: F401
     BF16, F16, KVHError, Loader, blob_size, copy_probe, decode, decode_batch, decode_kept, encode, encode_batch,
     encode_chunked, encode_kept, kept_tokens, level_bits, lib, make_dec_items, make_enc_items, make_tc_items, num_levels,
-    strerror, transcode, transcode_batch,
+    policy_marginal_utility_drop, policy_plan, policy_utility, strerror, transcode, transcode_batch,
 )

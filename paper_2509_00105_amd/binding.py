@@ -33,6 +33,10 @@ TC_ITEM = np.dtype([("src", "<u8"), ("dst", "<u8"), ("n_tokens", "<i4"), ("level
                     ("reserved", "<i4")], align=True)
 LOAD_ITEM = np.dtype([("blob_host", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"),
                       ("page_table", "<u8")], align=True)  # a HOST array, unlike the three above
+POLICY_ENTRY = np.dtype([("freq", "<f8"), ("first", "<i4"), ("n_choices", "<i4"), ("min_choice", "<i4"),
+                         ("reserved", "<i4")], align=True)
+POLICY_TIER = np.dtype([("bandwidth", "<f8"), ("capacity", "<f8")], align=True)
+assert POLICY_ENTRY.itemsize == 24 and POLICY_TIER.itemsize == 16
 assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32 and LOAD_ITEM.itemsize == 32
 
 _lib = None
@@ -83,6 +87,13 @@ def lib() -> ctypes.CDLL:
         L.kvh_loader_run.argtypes = [vp, vp, i32, i32, i32, i32, view, i32, vp, vp]
         L.kvh_loader_destroy.restype = i32
         L.kvh_loader_destroy.argtypes = [vp]
+        f64 = ctypes.c_double
+        L.kvh_policy_utility.restype = f64
+        L.kvh_policy_utility.argtypes = [f64] * 5
+        L.kvh_policy_marginal_utility_drop.restype = f64
+        L.kvh_policy_marginal_utility_drop.argtypes = [f64] * 4
+        L.kvh_policy_plan.restype = i32
+        L.kvh_policy_plan.argtypes = [vp, i32, vp, vp, i32, vp, i32, f64, vp, vp, ctypes.POINTER(f64)]
         L.kvh_copy_probe.restype = i32
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_strerror.restype = ctypes.c_char_p
@@ -366,6 +377,40 @@ class Loader:
             self.close()
         except Exception:
             pass
+
+
+def policy_utility(freq: float, alpha: float, quality: float, size_bytes: float, bandwidth: float) -> float:
+    return lib().kvh_policy_utility(freq, alpha, quality, size_bytes, bandwidth)
+
+
+def policy_marginal_utility_drop(u_m: float, u_n: float, size_m: float, size_n: float) -> float:
+    return lib().kvh_policy_marginal_utility_drop(u_m, u_n, size_m, size_n)
+
+
+def policy_plan(freqs, sizes, qualities, alpha: float, tiers, min_choices=None):
+    """kvh_policy_plan.  sizes / qualities: one sequence per entry (choices by decreasing size); tiers: sequence of
+    (bandwidth bytes/s, capacity bytes).  -> (tier per entry or -1, choice per entry or -1, total utility)."""
+    n = len(freqs)
+    ent = np.zeros(n, dtype=POLICY_ENTRY)
+    counts = np.array([len(s) for s in sizes], dtype=np.int64)
+    ent["freq"] = freqs
+    ent["n_choices"] = counts
+    ent["first"] = np.concatenate([[0], np.cumsum(counts)[:-1]]) if n else []
+    ent["min_choice"] = 0 if min_choices is None else min_choices
+    flat_s = np.ascontiguousarray(np.concatenate([np.asarray(s, dtype=np.float64) for s in sizes]))
+    flat_q = np.ascontiguousarray(np.concatenate([np.asarray(q, dtype=np.float64) for q in qualities]))
+    if flat_q.size != flat_s.size:
+        raise ValueError("sizes and qualities must have the same shape")
+    tr = np.zeros(len(tiers), dtype=POLICY_TIER)
+    tr["bandwidth"] = [t[0] for t in tiers]
+    tr["capacity"] = [t[1] for t in tiers]
+    tier_out = np.empty(n, dtype=np.int32)
+    choice_out = np.empty(n, dtype=np.int32)
+    total = ctypes.c_double()
+    _check(lib().kvh_policy_plan(ent.ctypes.data, n, flat_s.ctypes.data, flat_q.ctypes.data, int(flat_s.size),
+                                 tr.ctypes.data, len(tiers), alpha, tier_out.ctypes.data, choice_out.ctypes.data,
+                                 ctypes.byref(total)), "kvh_policy_plan")
+    return tier_out, choice_out, total.value
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

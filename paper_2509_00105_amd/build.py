@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvh.so")
-SOURCES = ["kvh_api.hip", "kvh_decode.hip", "kvh_encode.hip", "kvh_transcode.hip", "kvh_loader.hip"]
+SOURCES = ["kvh_api.hip", "kvh_decode.hip", "kvh_encode.hip", "kvh_transcode.hip", "kvh_loader.hip", "kvh_policy.cpp"]
 
 # -ffp-contract=off: the codec's arithmetic fuses only where the source says fma.
 # -fno-honor-nans: inputs are finite by contract; without it every min/max of a value unpacked with

@@ -36,7 +36,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert set(names) >= {"kvh_encode", "kvh_decode", "kvh_encode_batch", "kvh_decode_batch", "kvh_encode_chunked",
                           "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe",
                           "kvh_kept_tokens", "kvh_encode_kept", "kvh_decode_kept", "kvh_transcode", "kvh_transcode_batch",
-                          "kvh_loader_create", "kvh_loader_run", "kvh_loader_destroy", "kvh_loader_slot_bytes"}
+                          "kvh_loader_create", "kvh_loader_run", "kvh_loader_destroy", "kvh_loader_slot_bytes",
+                          "kvh_policy_plan", "kvh_policy_utility", "kvh_policy_marginal_utility_drop"}
     for n in names:
         assert hasattr(lib, n), n
 
