@@ -202,3 +202,78 @@ def test_config5_mixed_batch_paged_decode(kvh):
     ragged = [i for i, (_, n) in enumerate(spans) if n % 128][:3]
     picks = sorted(set(ragged + [0, len(spans) // 2, len(spans) - 1]))
     oracle_check_chunks(kv, contiguous, blobs, picks, spans, levels, sizes, offs, dt, l, c)
+
+
+def test_config2_transcode_token_dropping_and_load_path_at_full_size(kvh):
+    """The widened paths on the benchmark's workload and launch configuration: fused transcode of all 32 chunks
+    (sampled chunks against the oracle's decode-then-encode; m -> m is the identity over every byte), token
+    dropping of the whole 8192-token entry (sampled layers against the oracle), and the pipelined load path
+    (bit-identical to the plain batched decode of the same blobs)."""
+    cfg = gen.CONFIGS["llama3_8b_8k"]
+    l, N, c, dt, chunk = cfg.l, cfg.n, cfg.c, cfg.dtype, cfg.chunk
+    tdt = torch.float16 if dt == F16 else torch.bfloat16
+    kv = gen.make_kv_device(l, N, c, dt, cfg.seed)
+    n_chunks = N // chunk
+    enc = {}
+    for level in (0, 1):
+        spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: level)
+        enc[level] = (encode_all(kvh, kv, spans, levels, sizes, offs, chunk), sizes[0])
+    torch.cuda.synchronize()
+
+    # --- transcode ---
+    for a, b in ((0, 1), (0, 2), (1, 2), (1, 1)):
+        src, size_a = enc[a]
+        size_b = kvh.blob_size(l, chunk, c, b)
+        dst = torch.zeros(n_chunks * size_b, dtype=torch.uint8, device="cuda")
+        status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
+        items = kvh.make_tc_items([src.data_ptr() + i * size_a for i in range(n_chunks)],
+                                  [dst.data_ptr() + i * size_b for i in range(n_chunks)], [chunk] * n_chunks,
+                                  [a] * n_chunks, [b] * n_chunks, "cuda")
+        kvh.transcode_batch(items, n_chunks, chunk, tdt, l, c, status=status)
+        torch.cuda.synchronize()
+        assert int(status.abs().sum().item()) == 0
+        if a == b:
+            assert torch.equal(dst, src)
+            continue
+        for ci in (0, 13, n_chunks - 1):
+            want = oracle.transcode(src[ci * size_a:(ci + 1) * size_a].cpu().numpy(), dt, l, chunk, c, a, b)
+            assert np.array_equal(dst[ci * size_b:(ci + 1) * size_b].cpu().numpy(), want), (a, b, ci)
+
+    # --- token dropping: the whole tensor as one entry, half of it kept ---
+    sink, window = 128, N // 2 - 128
+    n_kept = kvh.kept_tokens(N, sink, window)
+    blob = kvh.encode_kept(kv[0], kv[1], sink, window, 2)
+    out = torch.zeros_like(kv)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kvh.decode_kept(blob, 2, N, sink, window, out[0], out[1], status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    assert not out[:, :, sink:N - window].any()  # dropped rows untouched
+    host = bits(kv[:, [0, l - 1]])               # first and last layer through the oracle
+    want_blob = oracle.encode_kept(host[0], host[1], dt, sink, window, 2)
+    off_g = oracle.section_offsets(l, n_kept, c, 2, l - 1)
+    off_w = oracle.section_offsets(2, n_kept, c, 2, 1)
+    layer_bytes = (blob.numel() - 64) // l
+    got = blob.cpu().numpy()
+    assert np.array_equal(got[64:64 + layer_bytes], want_blob[64:64 + layer_bytes])
+    assert np.array_equal(got[off_g["kmeta"]:off_g["kmeta"] + layer_bytes], want_blob[off_w["kmeta"]:off_w["kmeta"] + layer_bytes])
+    wk = np.zeros((2, N, c), np.uint16); wv = np.zeros_like(wk)
+    assert oracle.decode_kept_into(want_blob, dt, 2, N, c, sink, window, 2, wk, wv) == 0
+    assert np.array_equal(bits(out[0][[0, l - 1]]), wk) and np.array_equal(bits(out[1][[0, l - 1]]), wv)
+
+    # --- load path: 32 blobs from pinned host memory, two slots of four ---
+    src, size = enc[0]
+    spans, levels, sizes, offs = chunk_plan(kvh, l, N, c, chunk, lambda i: 0)
+    plain = decode_all(kvh, src, spans, levels, offs, chunk, torch.zeros_like(kv))
+    host_all = torch.empty(src.numel(), dtype=torch.uint8).pin_memory()
+    host_all.copy_(src)
+    staging = torch.empty(2 * (4 * size + 1024), dtype=torch.uint8, device="cuda")
+    ld = kvh.Loader(staging, 2)
+    piped = torch.zeros_like(kv)
+    status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
+    ld.run([host_all[i * size:(i + 1) * size] for i in range(n_chunks)], [chunk] * n_chunks, [0] * n_chunks,
+           [i * chunk for i in range(n_chunks)], piped[0], piped[1], status=status)
+    torch.cuda.synchronize()
+    ld.close()
+    assert int(status.abs().sum().item()) == 0
+    assert torch.equal(piped.view(torch.int16), plain.view(torch.int16))
