@@ -15,7 +15,10 @@
 // consecutive channels, so a wave moves one whole code row of the span per access (16 / 8 / 4
 // bytes per lane at 8 / 4 / 2 bits).  K parameters (per channel) are prepared once per block,
 // two channels per thread, and shared through LDS; V parameters (per token and head) are
-// prepared by one lane per group and broadcast inside the wave.
+// prepared by one lane per group and broadcast inside the wave.  When the whole code -> code map
+// of a group fits one register (4 -> 2 and the pairs that start from 2 bits) the "parameters"
+// are that map, built by running the arithmetic once per input code, and an element costs a
+// shift and a funnel shift.
 #include <type_traits>
 
 #include "kvh_common.hpp"
@@ -223,6 +226,86 @@ __device__ __forceinline__ void transcode_row(uint8_t* out, const InCodes<BI>& c
   store_codes16<BO>(out, t);
 }
 
+// ---- narrow inputs: one small table per group ---------------------------------------------------
+// With b_in <= 4 a group has at most 16 distinct input codes, so its whole code -> code map fits one
+// register when 2^b_in * b_out <= 32 (4 -> 2, 2 -> 2, 2 -> 4, 2 -> 8).  The map is built by running
+// the arithmetic above once per input code; an element then costs a shift and a funnel shift
+// instead of seven floating-point instructions.
+template <int BI, int BO>
+constexpr bool kUseTable = (1 << BI) * BO <= 32;
+
+template <int DT, int BI, int BO>
+__device__ __forceinline__ uint32_t code_table(uint32_t meta, uint32_t& out_meta) {
+  constexpr int NQ = 1 << BI;
+  bool fix;
+  const TcParams p = tc_params<DT, BI, BO>(meta, out_meta, fix);
+  uint32_t table = 0;
+#pragma unroll
+  for (int q = 0; q < NQ; q += 2) {
+    const uint32_t pk = pack2<DT>(recon((float)q, p.scale, p.mn), recon((float)(q + 1), p.scale, p.mn));
+    const float x0 = t16_to_f32<DT>(pk & 0xffffu);
+    const float x1 = q + 1 == NQ - 1 ? p.top : t16_to_f32<DT>(pk >> 16);  // the top code decodes to the stored maximum
+    const uint32_t two = __builtin_amdgcn_cvt_pk_u8_f32((x1 - p.mn) * p.inv, 1,
+                                                        __builtin_amdgcn_cvt_pk_u8_f32((x0 - p.mn) * p.inv, 0, 0u));
+    table |= ((two & 0xffu) | ((two >> 8) & 0xffu) << BO) << (BO * q);
+  }
+  return table;
+}
+
+// Byte-wise shift amounts b_out * q for the 16 codes of a lane: code j sits in byte sh_byte(j) of
+// e[sh_word(j)].
+template <int BI, int BO>
+struct Shifts;
+template <int BO>
+struct Shifts<4, BO> {
+  static constexpr int S = BO == 2 ? 1 : BO == 4 ? 2 : 3;
+  static constexpr uint32_t M = 0x0f0f0f0fu << S;
+  static __device__ __forceinline__ void make(const InCodes<4>& cw, uint32_t (&e)[4]) {
+    e[0] = opaque((cw.w.x << S) & M);
+    e[1] = opaque((cw.w.x >> (4 - S)) & M);
+    e[2] = opaque((cw.w.y << S) & M);
+    e[3] = opaque((cw.w.y >> (4 - S)) & M);
+  }
+  static constexpr int word(int j) { return (j >> 3) * 2 + (j & 1); }
+  static constexpr int byte(int j) { return (j & 7) >> 1; }
+};
+template <int BO>
+struct Shifts<2, BO> {
+  static constexpr int S = BO == 2 ? 1 : BO == 4 ? 2 : 3;
+  static constexpr uint32_t M = 0x03030303u << S;
+  static __device__ __forceinline__ void make(const InCodes<2>& cw, uint32_t (&e)[4]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) e[k] = opaque((2 * k >= S ? cw.w >> (2 * k - S) : cw.w << (S - 2 * k)) & M);
+  }
+  static constexpr int word(int j) { return j & 3; }
+  static constexpr int byte(int j) { return j >> 2; }
+};
+
+// One row of a lane through the tables.  table(j) gives the table of channel j.
+template <int BI, int BO, typename T>
+__device__ __forceinline__ void lookup_row(uint8_t* out, const InCodes<BI>& cw, T&& table) {
+  using Sh = Shifts<BI, BO>;
+  constexpr int kPer = 32 / BO;  // codes per output word
+  uint32_t e[4];
+  Sh::make(cw, e);
+  uint32_t acc[kTcLaneCh / kPer] = {};
+#pragma unroll
+  for (int j = 0; j < kTcLaneCh; ++j) {
+    const uint32_t x = table(j) >> ((e[Sh::word(j)] >> (8 * Sh::byte(j))) & 0xffu);
+    // funnel shift: the low b_out bits of x enter at the top; after kPer steps code j sits at bit b_out * (j % kPer)
+    acc[j / kPer] = __builtin_amdgcn_alignbit(x, acc[j / kPer], BO);
+  }
+  if constexpr (BO == 2) {
+    gstore_stream<uint32_t>(out, acc[0]);
+  } else if constexpr (BO == 4) {
+    uintx2 o = {acc[0], acc[1]};
+    gstore_stream<uintx2>(out, o);
+  } else {
+    uintx4 o = {acc[0], acc[1], acc[2], acc[3]};
+    gstore_stream<uintx4>(out, o);
+  }
+}
+
 struct HeaderWords {
   uintx4 a, b, c;
 };
@@ -266,10 +349,13 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
   const uint8_t* in_codes = in_layer + gi.kmeta + (is_v ? gi.codes + gi.vmeta : 0) + ch * BI / 8;
   uint8_t* out_codes = out_layer + go.kmeta + (is_v ? go.codes + go.vmeta : 0) + ch * BO / 8;
 
-  // Rows in flight per wave.  A K wave also holds the parameters of its 16 channels (48 registers),
-  // so with 8-bit input (4 registers per row) it takes half as many rows at a time.
-  constexpr int kRowsK = BI == 8 ? kTcBatch / 2 : kTcBatch;
-  InCodes<BI> cw[kTcBatch];
+  // Rows in flight per wave.  Narrow codes (2 registers a row or less) are loaded for all 16 rows of
+  // the wave at once: one round trip to memory instead of two, and twice the bytes in flight.  With
+  // 8-bit input a row takes 4 registers; a K wave also holds the parameters of its 16 channels
+  // (48 registers), so it takes 4 rows at a time and a V wave 8.
+  constexpr int kRowsK = BI == 8 ? kTcBatch / 2 : kTcRows;
+  constexpr int kRowsV = BI == 8 ? kTcBatch : kTcRows;
+  InCodes<BI> cw[kRowsV];
   auto load_batch = [&](int t0, auto rows_tag) {
 #pragma unroll
     for (int i = 0; i < decltype(rows_tag)::value; ++i) {
@@ -278,19 +364,24 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
       cw[i].load(in_codes + (size_t)t * gi.row_bytes);
     }
   };
-  auto run_batch = [&](int t0, auto rows_tag, auto fix_tag, auto&& param_of) {
+  // rows t0 .. t0 + rows - 1, held in cw[first ..]
+  auto run_batch = [&](int t0, auto first_tag, auto rows_tag, auto fix_tag, auto&& param_of) {
     constexpr bool FIX = decltype(fix_tag)::value;
+    constexpr int kFirst = decltype(first_tag)::value;
 #pragma unroll
     for (int i = 0; i < decltype(rows_tag)::value; ++i) {
       if (t0 + i < n) {  // wave-uniform
         auto param = param_of(i);  // may shuffle across lanes: taken with the whole wave enabled
-        if (active) transcode_row<DT, BI, BO, FIX>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[i], param);
+        if (active) transcode_row<DT, BI, BO, FIX>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[kFirst + i], param);
       }
       __builtin_amdgcn_sched_barrier(0);  // one row at a time: keeps the temporaries of different rows apart
     }
   };
+  using Zero = std::integral_constant<int, 0>;
+  using Eight = std::integral_constant<int, kTcBatch>;
+  using Batch = std::integral_constant<int, kTcBatch>;
   using RowsK = std::integral_constant<int, kRowsK>;
-  using RowsV = std::integral_constant<int, kTcBatch>;
+  using RowsV = std::integral_constant<int, kRowsV>;
 
   // The caller guarantees kvh_blob_size(l, n_tokens, c, level_in) readable bytes at the source,
   // so the loads issued before the header verdict stay inside the buffer whatever it says.
@@ -329,9 +420,33 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
   }
 
   if (!is_v) {
-    bool fix = false;
     uint32_t om[2] = {0u, 0u};
     const uint32_t meta[2] = {km.x, km.y};
+    if constexpr (kUseTable<BI, BO>) {
+      uint32_t* ktab = reinterpret_cast<uint32_t*>(kpar);  // [slot][lane], one word per channel
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int lc = (int)threadIdx.x * 2 + e;
+        ktab[(lc % kTcLaneCh) * kWave + lc / kTcLaneCh] = code_table<DT, BI, BO>(meta[e], om[e]);
+      }
+      if (pact) {
+        uintx2 o = {om[0], om[1]};
+        gstore<uintx2>(out_layer + ((size_t)g * c + pc) * 4, o);
+      }
+      __syncthreads();
+      if (t_first >= n) return;  // wave-uniform, after the barrier
+      uint32_t tab[kTcLaneCh];
+#pragma unroll
+      for (int j = 0; j < kTcLaneCh; ++j) tab[j] = ktab[j * kWave + lane];
+#pragma unroll
+      for (int i = 0; i < kRowsK; ++i) {  // kRowsK == kTcRows here: the wave's rows are all loaded
+        if (t_first + i < n && active)
+          lookup_row<BI, BO>(out_codes + (size_t)(t_first + i) * go.row_bytes, cw[i], [&tab](int j) { return tab[j]; });
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      return;
+    }
+    bool fix = false;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       bool f;
@@ -362,7 +477,7 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
       auto param_of = [&](int) { return [&p](int j) -> const TcParams& { return p[j]; }; };
 #pragma unroll 1
       for (int t0 = t_first;;) {
-        run_batch(t0, RowsK{}, fix_tag, param_of);
+        run_batch(t0, Zero{}, RowsK{}, fix_tag, param_of);
         t0 += kRowsK;
         if (t0 >= t_first + kTcRows || t0 >= n) break;
         load_batch(t0, RowsK{});
@@ -373,33 +488,76 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
     if (t_first >= n) return;  // wave-uniform; V waves never meet at a barrier
     const uint8_t* in_vmeta = in_layer + gi.kmeta + gi.codes;
     uint8_t* out_vmeta = out_layer + go.kmeta + go.codes;
-#pragma unroll 1
-    for (int t0 = t_first;;) {
-      // lane -> the group (row t0 + lane / 8, head lane % 8 of this span)
-      const int t = t0 + lane / kTcSpanHeads;
-      const int head = span * kTcSpanHeads + lane % kTcSpanHeads;
-      TcParams mine = {0.0f, 0.0f, 0.0f, 0.0f};
-      bool fix = false;
-      if (t < n && head < heads) {
-        const size_t off = ((size_t)t * heads + head) * 4;
-        uint32_t om;
-        mine = tc_params<DT, BI, BO>(gload<uint32_t>(in_vmeta + off), om, fix);
-        gstore<uint32_t>(out_vmeta + off, om);
+    if constexpr (kUseTable<BI, BO>) {
+      // the wave's 16 rows are loaded; their groups are prepared 8 rows (= 64 groups, one per lane) at a time
+      uint32_t vm[2] = {0u, 0u};
+      bool own[2];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        const int t = t_first + sb * kTcBatch + lane / kTcSpanHeads;
+        const int head = span * kTcSpanHeads + lane % kTcSpanHeads;
+        own[sb] = t < n && head < heads;
+        if (own[sb]) vm[sb] = gload<uint32_t>(in_vmeta + ((size_t)t * heads + head) * 4);
       }
-      const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-      auto param_of = [&](int i) {
-        const int owner = i * kTcSpanHeads + lane / (kGroup / kTcLaneCh);
-        TcParams p;
-        p.mn = __shfl(mine.mn, owner);
-        p.scale = __shfl(mine.scale, owner);
-        p.inv = __shfl(mine.inv, owner);
-        p.top = __shfl(mine.top, owner);
-        return [p](int) -> const TcParams& { return p; };
+      auto eight_rows = [&](auto sb_tag) {
+        constexpr int sb = decltype(sb_tag)::value;
+        const int t0 = t_first + sb * kTcBatch;
+        uint32_t mine = 0;
+        if (own[sb]) {
+          const int t = t0 + lane / kTcSpanHeads;
+          const int head = span * kTcSpanHeads + lane % kTcSpanHeads;
+          uint32_t om;
+          mine = code_table<DT, BI, BO>(vm[sb], om);
+          gstore<uint32_t>(out_vmeta + ((size_t)t * heads + head) * 4, om);
+        }
+#pragma unroll
+        for (int i = 0; i < kTcBatch; ++i) {
+          if (t0 + i < n) {  // wave-uniform; the shuffle is taken with the whole wave enabled
+            const uint32_t tab = __shfl(mine, i * kTcSpanHeads + lane / (kGroup / kTcLaneCh));
+            if (active)
+              lookup_row<BI, BO>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[sb * kTcBatch + i], [tab](int) { return tab; });
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       };
-      if (any_fix) run_batch(t0, RowsV{}, Yes{}, param_of); else run_batch(t0, RowsV{}, No{}, param_of);
-      t0 += kTcBatch;
-      if (t0 >= t_first + kTcRows || t0 >= n) break;
-      load_batch(t0, RowsV{});
+      eight_rows(std::integral_constant<int, 0>{});
+      if (t_first + kTcBatch < n) eight_rows(std::integral_constant<int, 1>{});
+    } else {
+#pragma unroll 1
+      for (int t0 = t_first;;) {  // kRowsV rows from t0 on are loaded
+        auto eight_rows = [&](auto first_tag) {
+          const int tb = t0 + decltype(first_tag)::value;
+          // lane -> the group (row tb + lane / 8, head lane % 8 of this span)
+          const int t = tb + lane / kTcSpanHeads;
+          const int head = span * kTcSpanHeads + lane % kTcSpanHeads;
+          TcParams mine = {0.0f, 0.0f, 0.0f, 0.0f};
+          bool fix = false;
+          if (t < n && head < heads) {
+            const size_t off = ((size_t)t * heads + head) * 4;
+            uint32_t om;
+            mine = tc_params<DT, BI, BO>(gload<uint32_t>(in_vmeta + off), om, fix);
+            gstore<uint32_t>(out_vmeta + off, om);
+          }
+          const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+          auto param_of = [&](int i) {
+            const int owner = i * kTcSpanHeads + lane / (kGroup / kTcLaneCh);
+            TcParams p;
+            p.mn = __shfl(mine.mn, owner);
+            p.scale = __shfl(mine.scale, owner);
+            p.inv = __shfl(mine.inv, owner);
+            p.top = __shfl(mine.top, owner);
+            return [p](int) -> const TcParams& { return p; };
+          };
+          if (any_fix) run_batch(tb, first_tag, Batch{}, Yes{}, param_of); else run_batch(tb, first_tag, Batch{}, No{}, param_of);
+        };
+        eight_rows(Zero{});
+        if constexpr (kRowsV > kTcBatch) {
+          if (t0 + kTcBatch < n) eight_rows(Eight{});
+        }
+        t0 += kRowsV;
+        if (t0 >= t_first + kTcRows || t0 >= n) break;
+        load_batch(t0, RowsV{});
+      }
     }
     // zero the padding that rounds the vmeta section up to 16 bytes
     if (span == 0 && threadIdx.x == 0 && (g + 1) * kGroup >= n) {
