@@ -2,14 +2,15 @@
 // write fp16/bf16 KV rows, contiguous or through a page table (the "decompression" whose
 // overhead the paper's estimator profiles; Design section).
 //
-// Pure streaming kernel, no LDS and no block-level cooperation: the unit of work is one wave
-// decoding 8 consecutive token rows of a 1024-channel span (two 512-channel segments), i.e. 16 KiB
-// of contiguous output when c = 1024.  A lane owns 8 channels per segment, so each store is one
-// 128-bit access and the wave writes 1 KiB of a row per instruction.  K metadata
-// (per channel) is turned into fp32 parameters once per unit and stays in registers; V
-// metadata (per token and head) is prepared by one lane per group and broadcast.  The rare
-// groups whose top code does not land exactly on the stored maximum select a slower row loop
-// through a wave-uniform branch.
+// Streaming kernel.  The unit of work is one wave decoding 8 consecutive token rows of a
+// 1024-channel span (two 512-channel segments), i.e. 16 KiB of contiguous output when c = 1024.
+// A lane owns 8 channels per segment, so each store is one 128-bit access and the wave writes
+// 1 KiB of a row per instruction.  A block is 8 such units: 64 consecutive rows of one span, which
+// always lie in one K token-group.  K metadata (per channel) is therefore turned into fp32
+// parameters once per block, two channels per thread, and handed to the waves through 12 KiB of
+// LDS; V metadata (per token and head) is prepared by one lane per group and broadcast inside the
+// wave, and V blocks never meet at a barrier.  The rare groups whose top code does not land
+// exactly on the stored maximum select a slower row loop through a uniform branch.
 #include <type_traits>
 
 #include "kvh_common.hpp"
@@ -22,23 +23,14 @@ namespace kvh {
 #ifndef KVH_DEC_NTL
 #define KVH_DEC_NTL 0  // non-temporal loads of the packed codes
 #endif
-#ifndef KVH_DEC_WAVES
-#define KVH_DEC_WAVES 8  // waves per block (waves are independent; this only shapes dispatch)
-#endif
-constexpr int kDecWaves = KVH_DEC_WAVES;
+constexpr int kDecWaves = 8;                                     // units per block
 constexpr int kDecThreads = kDecWaves * kWave;
-
-#ifndef KVH_DEC_SWAP
-#define KVH_DEC_SWAP 0  // 1: grid = (units, items, 2l) so that consecutive blocks walk one layer's rows across chunks
-#endif
-#ifndef KVH_DEC_SEGS
-#define KVH_DEC_SEGS 2  // 512-channel segments per wave: 1 = half a 1024-channel row, 2 = the whole row
-#endif
-constexpr int kDecSegs = KVH_DEC_SEGS;
+constexpr int kDecSegs = 2;                                      // 512-channel segments per wave
 constexpr int kDecSpanCh = kDecSegs * kStripCh;                 // channels covered by one wave
 constexpr int kDecHeads = kDecSpanCh / kGroup;                  // V groups per row of a unit
 constexpr int kDecRows = kWave / kDecHeads;                     // token rows per wave: one lane per V group
-static_assert(kGroup % kDecRows == 0, "a unit must not straddle K token-groups");
+static_assert(kGroup % (kDecRows * kDecWaves) == 0, "a block must not straddle K token-groups");
+static_assert(kDecThreads * 2 == kDecSpanCh, "a thread prepares two K channels of the block's span");
 
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -170,7 +162,7 @@ __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int
 // blob pointer, so these loads stay inside the buffer whatever the header says.
 template <int DT, int BITS>
 __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
-                                            int t0, int span) {
+                                            int t0, int span, float* kshare, int t0_block) {
   const int lane = threadIdx.x & (kWave - 1);
   const int n = it.n_tokens;
   const int c = a.c;
@@ -206,17 +198,15 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   const uint8_t* codes = is_v ? vcodes : kcodes;
   const int heads = c / kGroup;
 
-  // metadata: K = the lane's 8 channels per segment; V = group (row lane / H, head lane % H) of this unit
-  uintx4 km[kDecSegs][2];
+  // metadata: K = the two channels of the span this thread prepares for the whole block;
+  // V = group (row lane / H, head lane % H) of this unit
   uint32_t vm = 0;
   bool v_owner = false;
+  uintx2 kpair = {0u, 0u};
+  const int pc = span * kDecSpanCh + (int)threadIdx.x * 2;
+  const bool pact = !is_v && pc < c;
   if (!is_v) {
-#pragma unroll
-    for (int s = 0; s < kDecSegs; ++s) {
-      const uint8_t* mp = kmeta + ((size_t)(t0 / kGroup) * c + ch[s]) * 4;
-      km[s][0] = gload<uintx4>(mp);
-      km[s][1] = gload<uintx4>(mp + 16);
-    }
+    if (pact) kpair = gload<uintx2>(kmeta + ((size_t)(t0_block / kGroup) * c + pc) * 4);
   } else {
     int t = t0 + lane / kDecHeads;
     int head = span * kDecHeads + lane % kDecHeads;
@@ -261,22 +251,39 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   using No = std::integral_constant<bool, false>;
 
   if (!is_v) {
+    // Every thread of the block prepares two channels of the span; the three arrays (minimum, scale,
+    // top code) meet in LDS and every wave then picks up the 16 channels its lanes own.  All waves of
+    // a K block reach the barrier, also those whose rows lie past the end of the blob.
     GroupParams gp[kDecSegs][kLaneCh];
     bool fix = false;
+    {
+      const uint32_t meta[2] = {kpair.x, kpair.y};
 #pragma unroll
-    for (int s = 0; s < kDecSegs; ++s) {
-      const uint32_t meta[8] = {km[s][0].x, km[s][0].y, km[s][0].z, km[s][0].w,
-                                km[s][1].x, km[s][1].y, km[s][1].z, km[s][1].w};
-#pragma unroll
-      for (int j = 0; j < kLaneCh; ++j) {
-        gp[s][j] = decode_params<DT, BITS>(meta[j]);
-        fix |= top_needs_fix<DT, BITS>(gp[s][j]);
+      for (int e = 0; e < 2; ++e) {
+        GroupParams p = decode_params<DT, BITS>(meta[e]);
+        fix |= pact && top_needs_fix<DT, BITS>(p);
+        const int lc = (int)threadIdx.x * 2 + e;
+        kshare[lc] = p.mn;
+        kshare[kDecSpanCh + lc] = p.scale;
+        kshare[2 * kDecSpanCh + lc] = __builtin_bit_cast(float, p.top);
       }
     }
-    const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+    const bool any_fix = __syncthreads_or(fix);
+    if (t0 >= n) return;  // wave-uniform, after the barrier
+#pragma unroll
+    for (int s = 0; s < kDecSegs; ++s) {
+      const int base = s * kStripCh + lane * kLaneCh;
+#pragma unroll
+      for (int j = 0; j < kLaneCh; ++j) {
+        gp[s][j].mn = kshare[base + j];
+        gp[s][j].scale = kshare[kDecSpanCh + base + j];
+        gp[s][j].top = __builtin_bit_cast(uint32_t, kshare[2 * kDecSpanCh + base + j]);
+      }
+    }
     auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
     if (any_fix) run(Yes{}, param_of); else run(No{}, param_of);
   } else {
+    if (t0 >= n) return;  // wave-uniform; V waves never meet at a barrier
     GroupParams mine = {0.0f, 0.0f, 0u};
     bool fix = false;
     if (v_owner) {
@@ -297,11 +304,11 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   }
 }
 
-// grid = (ceil(units / waves per block), 2 * l, items); unit = (row tile, channel span), span fastest, one per wave.
+// grid = (64-row blocks x spans, 2 * l, items); span fastest; wave w of a block takes rows 8 w .. 8 w + 7 of its 64.
 template <int DT>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
-  const int item_idx = KVH_DEC_SWAP ? blockIdx.y : blockIdx.z;
-  const int lay_kv = KVH_DEC_SWAP ? blockIdx.z : blockIdx.y;
+  const int item_idx = blockIdx.z;
+  const int lay_kv = blockIdx.y;
   kvh_item it;
   if (a.items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
@@ -319,19 +326,19 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   it.level = uniform(it.level);
   it.dst_token0 = uniform(it.dst_token0);
   it.page_table = uniform(it.page_table);
+  __shared__ float kshare[3 * kDecSpanCh];  // K parameters of the block's span: minima, scales, top codes
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
-  const int unit = blockIdx.x * kDecWaves + wave;
-  const int tile = unit / nspans;
-  const int strip = unit - tile * nspans;
-  const int t0 = tile * kDecRows;
-  if (it.n_tokens < 1 || t0 >= it.n_tokens) return;
+  const int strip = blockIdx.x % nspans;
+  const int t0_block = (blockIdx.x / nspans) * (kDecWaves * kDecRows);
+  const int t0 = t0_block + wave * kDecRows;
+  if (it.n_tokens < 1 || t0_block >= it.n_tokens) return;  // block-uniform
   const int lam = lay_kv >> 1;
   const bool is_v = lay_kv & 1;
   switch (it.level) {
-    case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip); break;
-    case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip); break;
-    case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip); break;
+    case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
+    case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
+    case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
     default:
       if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
       break;
@@ -340,9 +347,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
-  const int64_t units = (int64_t)((max_tokens + kDecRows - 1) / kDecRows) * nspans;
-  const unsigned gx = (unsigned)((units + kDecWaves - 1) / kDecWaves);
-  dim3 grid = KVH_DEC_SWAP ? dim3(gx, (unsigned)n_items, (unsigned)(2 * a.l)) : dim3(gx, (unsigned)(2 * a.l), (unsigned)n_items);
+  const unsigned gx = (unsigned)(((max_tokens + kDecRows * kDecWaves - 1) / (kDecRows * kDecWaves)) * nspans);
+  dim3 grid(gx, (unsigned)(2 * a.l), (unsigned)n_items);
   if (dt == KVH_F16)
     hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, a);
   else
