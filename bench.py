@@ -217,7 +217,7 @@ def main():
     # DRAM tier); `pipelined` = kvh_loader_run with 2 staging slots (copy of group g+1 overlaps decode of group g),
     # `serial` = one copy of all blobs, then decode_batch; `uncompressed` = copying the 16-bit KV itself.  These
     # are the PCIe-inclusive figures of the path; they are not part of `value`.
-    load_path = []
+    load_path, store_path, store_ok = [], [], True
     with torch.cuda.stream(stream):
         host_unc = torch.empty(kv.numel() * 2, dtype=torch.uint8).pin_memory()
         host_unc.copy_(kv.view(torch.uint8).reshape(-1), non_blocking=False)
@@ -268,6 +268,33 @@ def main():
                                   "pcie_GBps": n_chunks * size / ms / 1e6,
                                   "uncompressed_GBps": 2 * l * N * c * 2 / ms / 1e6})
             assert int(status[level].abs().sum().item()) == 0
+
+            # The store direction (HBM -> DRAM tier): `direct` = encode_batch writing its blobs straight into the
+            # pinned host buffer; `serial` = encode_batch into HBM, then one copy of the blobs to the host.
+            host_items = kvh.make_enc_items([host_all.data_ptr() + i * size for i in range(n_chunks)],
+                                            [i * chunk for i in range(n_chunks)], [chunk] * n_chunks, [level] * n_chunks, dev)
+
+            def store_direct():
+                kvh.encode_batch(host_items, n_chunks, chunk, kv[0], kv[1], stream=stream)
+
+            def store_serial():
+                kvh.encode_batch(enc_items[level], n_chunks, chunk, kv[0], kv[1], stream=stream)
+                host_all.copy_(blobs[level], non_blocking=True)
+
+            for mode, fn in (("direct", store_direct), ("serial", store_serial)):
+                fn()
+                torch.cuda.synchronize()
+                le = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                le[0].record(stream)
+                for _ in range(3):
+                    fn()
+                le[1].record(stream)
+                torch.cuda.synchronize()
+                ms = le[0].elapsed_time(le[1]) / 3
+                store_path.append({"mode": mode, "bits": kvh.level_bits(level), "ms": ms,
+                                   "pcie_GBps": n_chunks * size / ms / 1e6,
+                                   "uncompressed_GBps": 2 * l * N * c * 2 / ms / 1e6})
+            store_ok = store_ok and bool(torch.equal(host_all, blobs[level].cpu()))
             del host_all, host_blobs, dev_all
         loader.close()
         del staging
@@ -361,6 +388,8 @@ def main():
         "token_dropping": dropping,
         "transcode": transcode,
         "load_path": load_path,
+        "store_path": store_path,
+        "store_path_blobs_identical": store_ok,
         "policy": policy,
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
         "step_ms_min": min(step_ms),

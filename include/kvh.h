@@ -27,7 +27,9 @@
  *
  * Conventions
  *   - Pointers named *_dev are DEVICE pointers owned by the caller; everything else is host
- *     memory.  The library allocates nothing, keeps no state, and frees nothing.
+ *     memory.  A blob pointer may also be pinned host memory that the device can address (the
+ *     kernels then read or write it over the bus: encoding or transcoding straight into the host
+ *     tier needs no staging copy).  The codec calls allocate nothing, keep no state, free nothing.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call only
  *     ENQUEUES kernels and returns; results are valid once the caller has synchronised the
  *     stream.  Device buffers must stay alive until then.

@@ -129,6 +129,13 @@ def _require_cuda(*tensors):
             raise ValueError("device tensor expected (the HIP path has no CPU fallback)")
 
 
+def _require_visible(*tensors):
+    """Blob buffers may live in HBM or in pinned host memory (both are addressable by the kernels)."""
+    for t in tensors:
+        if t is not None and not (t.is_cuda or t.is_pinned()):
+            raise ValueError("device tensor or pinned host tensor expected (pageable host memory is not visible to the GPU)")
+
+
 def _view(k: torch.Tensor, v: torch.Tensor, paged: bool = False):
     """kvh_kv_view of K/V tensors [l][tokens][c] (or [l][P][block][c] when paged)."""
     _require_cuda(k, v)
@@ -161,7 +168,7 @@ def encode(k: torch.Tensor, v: torch.Tensor, level: int, blob: torch.Tensor | No
         if size == 0:
             _check(lib().kvh_encode(ctypes.byref(view), dt, l, n, c, level, None, 0, None), "kvh_encode")
         blob = torch.empty(size, dtype=torch.uint8, device=k.device)
-    _require_cuda(blob)
+    _require_visible(blob)
     _check(lib().kvh_encode(ctypes.byref(view), dt, l, n, c, level, blob.data_ptr(), blob.numel(), _stream_ptr(stream)),
            "kvh_encode")
     return blob
@@ -254,7 +261,7 @@ def encode_kept(k: torch.Tensor, v: torch.Tensor, sink: int, window: int, level:
         if size == 0:
             _check(lib().kvh_encode_kept(ctypes.byref(view), dt, l, N, c, sink, window, level, None, 0, None), "kvh_encode_kept")
         blob = torch.empty(size, dtype=torch.uint8, device=k.device)
-    _require_cuda(blob)
+    _require_visible(blob)
     _check(lib().kvh_encode_kept(ctypes.byref(view), dt, l, N, c, sink, window, level, blob.data_ptr(), blob.numel(),
                                  _stream_ptr(stream)), "kvh_encode_kept")
     return blob
@@ -289,7 +296,8 @@ def _dt_code(dtype) -> int:
 def transcode(blob: torch.Tensor, dtype, l: int, n_tokens: int, c: int, level_in: int, level_out: int,
               out: torch.Tensor | None = None, status: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     """kvh_transcode: a blob of n_tokens stored tokens at level_in -> a blob at level_out (uint8 device tensor)."""
-    _require_cuda(blob, out, status)
+    _require_visible(blob, out)
+    _require_cuda(status)
     dt = _dt_code(dtype)
     if status is not None and status.dtype != torch.int32:
         raise ValueError("status must be int32")

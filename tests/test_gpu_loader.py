@@ -127,3 +127,31 @@ def test_loader_argument_errors(kvh):
     assert kvh.lib().kvh_loader_run(ld._h, a.ctypes.data, 1, 0, 1, 128, ctypes.byref(view), 16, None, None) == -1
     ld.close()
     torch.cuda.synchronize()
+
+
+def test_store_path_encode_straight_into_pinned_host_memory(kvh):
+    """The store direction needs no staging at all: a blob pointer may be any memory the device can write, so the
+    encoder writes its blobs straight into pinned host memory (the DRAM tier).  Byte for byte the oracle's blobs."""
+    dt, l, c, chunk = BF16, 2, 1024, 256
+    lens, levels = [256, 256, 130], [2, 0, 1]
+    N = sum(lens)
+    k, v = gen.make_kv(l, N, c, dt, seed=81)
+    kd = torch.from_numpy(k.view(np.int16)).cuda().view(torch.bfloat16)
+    vd = torch.from_numpy(v.view(np.int16)).cuda().view(torch.bfloat16)
+    sizes = [kvh.blob_size(l, n, c, lv) for n, lv in zip(lens, levels)]
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    host = torch.full((int(sum(sizes)),), 0xEE, dtype=torch.uint8).pin_memory()
+    t0s = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    items = kvh.make_enc_items([host.data_ptr() + int(o) for o in offs], t0s, lens, levels, "cuda")
+    kvh.encode_batch(items, 3, chunk, kd, vd)
+    torch.cuda.synchronize()
+    got = host.numpy()
+    for o, s, t0, n, lv in zip(offs, sizes, t0s, lens, levels):
+        want = oracle.encode(np.ascontiguousarray(k[:, t0:t0 + n]), np.ascontiguousarray(v[:, t0:t0 + n]), dt, lv)
+        assert np.array_equal(got[o:o + s], want), (t0, n, lv)
+    # and the fused transcode can demote a blob from HBM straight to the host tier
+    dev_blob = torch.from_numpy(got[offs[1]:offs[1] + sizes[1]].copy()).cuda()
+    low = torch.empty(kvh.blob_size(l, lens[1], c, 2), dtype=torch.uint8).pin_memory()
+    kvh.transcode(dev_blob, torch.bfloat16, l, lens[1], c, 0, 2, out=low)
+    torch.cuda.synchronize()
+    assert np.array_equal(low.numpy(), oracle.transcode(got[offs[1]:offs[1] + sizes[1]], dt, l, lens[1], c, 0, 2))
