@@ -163,6 +163,27 @@ def main():
             del err
         torch.cuda.synchronize()
 
+    # Outside the timed region: what one chunk costs on its own (the "decompression overhead" the paper's
+    # estimator profiles per entry): kvh_decode / kvh_encode of a single 256-token chunk, 100 calls back to back.
+    single = []
+    with torch.cuda.stream(stream):
+        st1c = torch.zeros(1, dtype=torch.int32, device=dev)
+        for level in range(3):
+            size = kvh.blob_size(l, chunk, c, level)
+            one = blobs[level][:size]
+            for name, fn in (("decode", lambda: kvh.decode(one, level, chunk, out[0], out[1], status=st1c, stream=stream)),
+                             ("encode", lambda: kvh.encode(kv[0], kv[1], level, blob=one, n_tokens=chunk, stream=stream))):
+                fn()
+                se = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                se[0].record(stream)
+                for _ in range(100):
+                    fn()
+                se[1].record(stream)
+                torch.cuda.synchronize()
+                single.append({"op": name, "bits": kvh.level_bits(level), "tokens": chunk,
+                               "us_per_call": se[0].elapsed_time(se[1]) * 10.0})
+        assert int(st1c.item()) == 0
+
     # Outside the timed region: the plain copy kernel over 1 GiB.  It gives the practical copy rate of
     # this device next to the codec's figures, and a dispatch of known size for scaling HBM counters.
     with torch.cuda.stream(stream):
@@ -398,6 +419,7 @@ def main():
         "decode_hbm_frac": {str(r["bits"]): r["hbm_frac"] for r in dec2},
         "kernels": per_kernel,
         "quality": quality,
+        "single_chunk": single,
         "paper_context": "the paper reports no encode/decode throughput; its end-to-end figures (1.43-2.4x delay saving at "
                          "equal quality, 6-55 % quality gain at equal delay) are for 1x NVIDIA A100, 100 GB DRAM, 400 GB SSD "
                          "at 1 GB/s, Llama-3.1-8B-Instruct on 1,100 LongBench contexts: context, not a target for this metric",
