@@ -267,7 +267,7 @@ def main():
                           "uncompressed_GBps": host_unc.numel() / unc_ms / 1e6})
         del host_unc
         n_slots = 2  # double buffering; a slot takes 4 chunks at 8 bits, 7 at 4 bits, 14 at 2 bits
-        staging = torch.empty(n_slots * (4 * kvh.blob_size(l, chunk, c, 0) + 1024), dtype=torch.uint8, device=dev)
+        staging = torch.empty(n_slots * (4 * kvh.blob_size(l, chunk, c, 0) + 1536), dtype=torch.uint8, device=dev)
         loader = kvh.Loader(staging, n_slots)
         for level in range(3):
             size = kvh.blob_size(l, chunk, c, level)

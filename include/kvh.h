@@ -170,6 +170,41 @@ int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int
                     const kvh_kv_view* dst, int64_t dst_token0, int compact, const int32_t* page_table_dev,
                     int block_tokens, int32_t* status_dev, void* stream);
 
+/* One token-dropping encode job of a batch.  The ARRAY of items lives in device memory. */
+typedef struct {
+  void* blob;          /* device pointer, 16-byte aligned, room for kvh_blob_size(l, kept tokens, c, level) */
+  int64_t src_token0;  /* first token of the entry in the source view */
+  int32_t orig_tokens; /* N: tokens of the entry */
+  int32_t sink;        /* first tokens kept */
+  int32_t window;      /* last tokens kept */
+  int32_t level;       /* 0 .. 2 */
+} kvh_kept_enc_item;
+
+/* kvh_encode_kept for many entries of one source view in ONE launch.  max_kept_tokens_per_item bounds
+ * kvh_kept_tokens(orig_tokens, sink, window) over the items.  The caller guarantees the items' validity
+ * (as for kvh_encode_batch); items with a bad level or nothing kept are skipped.  n_items <= 65535. */
+int kvh_encode_kept_batch(const kvh_kept_enc_item* items_dev, int n_items, int max_kept_tokens_per_item, kvh_dtype dt,
+                          int l, int c, const kvh_kv_view* src, void* stream);
+
+/* One decode job of a batch that may hold token-dropped blobs.  The ARRAY lives in device memory.  For an
+ * ordinary blob orig_tokens = sink = window = 0.  For a token-dropped blob they are the values it was encoded
+ * with and n_tokens = kvh_kept_tokens(orig_tokens, sink, window); compact as for kvh_decode_kept. */
+typedef struct {
+  const void* blob;          /* device pointer, 16-byte aligned */
+  int32_t n_tokens;          /* tokens stored in the blob, 1 .. max_tokens_per_item */
+  int32_t level;             /* level the blob was stored at */
+  int64_t dst_token0;        /* logical position of the entry's first token in its request */
+  const int32_t* page_table; /* device pointer to the request's table, or NULL for contiguous */
+  int32_t orig_tokens, sink, window;
+  int32_t compact;
+} kvh_kept_item;
+
+/* kvh_decode_batch over items that may be token-dropped (mixed with ordinary ones).  An item whose header
+ * disagrees, or whose n_tokens is not what (orig_tokens, sink, window) keep, gets KVH_DEV_HEADER_MISMATCH
+ * and writes nothing. */
+int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l,
+                          int c, const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
+
 /* ---- Transcode ------------------------------------------------------------------------------------
  * The paper's policy lowers the quality of stored entries step by step ("compress furthermore" from
  * rate m to rate n; Design section, marginal utility drop).  kvh_transcode re-compresses a stored blob
@@ -223,17 +258,20 @@ typedef struct {
   int32_t level;             /* level it was stored at */
   int64_t dst_token0;        /* logical position of its first token in the destination */
   const int32_t* page_table; /* DEVICE pointer to the request's table, or NULL for contiguous */
+  int32_t orig_tokens, sink, window; /* all 0 for an ordinary blob; else what the blob was token-dropped with,
+                                        and n_tokens = kvh_kept_tokens(orig_tokens, sink, window) */
+  int32_t compact;           /* as for kvh_decode_kept */
 } kvh_load_item;
 
 /* Create a loader over `staging_dev` (device memory, 16-byte aligned, staging_bytes long), cut into n_slots
- * equal slots (1..64; 2 = double buffering).  The first 1 KiB of a slot holds descriptors; the rest
+ * equal slots (1..64; 2 = double buffering).  The first 1.5 KiB of a slot holds descriptors; the rest
  * (kvh_loader_slot_bytes) must hold the largest blob that will be loaded and is best sized for several. */
 int kvh_loader_create(kvh_loader** out, void* staging_dev, size_t staging_bytes, int n_slots);
 /* Bytes a slot offers to blobs (0 for NULL). */
 size_t kvh_loader_slot_bytes(const kvh_loader* loader);
 /* Enqueue, group by group in item order: wait until the next slot is free, copy the group's blobs host ->
  * slot on the loader's copy stream, then decode them on `stream` into `dst` (contiguous or paged, as
- * kvh_decode_batch; token-dropped blobs are not accepted).  Returns once everything is enqueued; results
+ * kvh_decode_kept_batch: ordinary and token-dropped blobs may be mixed).  Returns once everything is enqueued; results
  * are valid after `stream` has been synchronised; host blobs and the staging buffer must stay alive until
  * then.  status_dev, if not NULL, has one zeroed int32 per item (KVH_DEV_HEADER_MISMATCH as for
  * kvh_decode_batch).  All items are validated before anything is enqueued. */

@@ -32,12 +32,18 @@ DEC_ITEM = np.dtype([("blob", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("d
 TC_ITEM = np.dtype([("src", "<u8"), ("dst", "<u8"), ("n_tokens", "<i4"), ("level_in", "<i4"), ("level_out", "<i4"),
                     ("reserved", "<i4")], align=True)
 LOAD_ITEM = np.dtype([("blob_host", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"),
-                      ("page_table", "<u8")], align=True)  # a HOST array, unlike the three above
+                      ("page_table", "<u8"), ("orig_tokens", "<i4"), ("sink", "<i4"), ("window", "<i4"),
+                      ("compact", "<i4")], align=True)  # a HOST array, unlike the others
+KEPT_ENC_ITEM = np.dtype([("blob", "<u8"), ("src_token0", "<i8"), ("orig_tokens", "<i4"), ("sink", "<i4"),
+                          ("window", "<i4"), ("level", "<i4")], align=True)
+KEPT_ITEM = np.dtype([("blob", "<u8"), ("n_tokens", "<i4"), ("level", "<i4"), ("dst_token0", "<i8"), ("page_table", "<u8"),
+                      ("orig_tokens", "<i4"), ("sink", "<i4"), ("window", "<i4"), ("compact", "<i4")], align=True)
 POLICY_ENTRY = np.dtype([("freq", "<f8"), ("first", "<i4"), ("n_choices", "<i4"), ("min_choice", "<i4"),
                          ("reserved", "<i4")], align=True)
 POLICY_TIER = np.dtype([("bandwidth", "<f8"), ("capacity", "<f8")], align=True)
 assert POLICY_ENTRY.itemsize == 24 and POLICY_TIER.itemsize == 16
-assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32 and LOAD_ITEM.itemsize == 32
+assert ENC_ITEM.itemsize == 24 and DEC_ITEM.itemsize == 32 and TC_ITEM.itemsize == 32 and LOAD_ITEM.itemsize == 48
+assert KEPT_ENC_ITEM.itemsize == 32 and KEPT_ITEM.itemsize == 48
 
 _lib = None
 
@@ -75,6 +81,10 @@ def lib() -> ctypes.CDLL:
         L.kvh_encode_kept.argtypes = [view, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         L.kvh_decode_kept.restype = i32
         L.kvh_decode_kept.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, view, i64, i32, vp, i32, vp, vp]
+        L.kvh_encode_kept_batch.restype = i32
+        L.kvh_encode_kept_batch.argtypes = [vp, i32, i32, i32, i32, i32, view, vp]
+        L.kvh_decode_kept_batch.restype = i32
+        L.kvh_decode_kept_batch.argtypes = [vp, i32, i32, i32, i32, i32, view, i32, vp, vp]
         L.kvh_transcode.restype = i32
         L.kvh_transcode.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, sz, vp, vp]
         L.kvh_transcode_batch.restype = i32
@@ -285,6 +295,48 @@ def decode_kept(blob: torch.Tensor, level: int, N: int, sink: int, window: int, 
            "kvh_decode_kept")
 
 
+def make_kept_enc_items(blob_ptrs, src_token0, orig_tokens, sinks, windows, levels, device) -> torch.Tensor:
+    """Upload an array of kvh_kept_enc_item (argument marshalling; returns a uint8 device tensor)."""
+    a = np.zeros(len(blob_ptrs), dtype=KEPT_ENC_ITEM)
+    a["blob"], a["src_token0"], a["orig_tokens"], a["sink"], a["window"], a["level"] = \
+        blob_ptrs, src_token0, orig_tokens, sinks, windows, levels
+    return torch.from_numpy(a.view(np.uint8).copy()).to(device)
+
+
+def make_kept_items(blob_ptrs, n_tokens, levels, dst_token0, page_table_ptrs, orig_tokens, sinks, windows, compact,
+                    device) -> torch.Tensor:
+    """Upload an array of kvh_kept_item (argument marshalling; returns a uint8 device tensor)."""
+    a = np.zeros(len(blob_ptrs), dtype=KEPT_ITEM)
+    a["blob"], a["n_tokens"], a["level"], a["dst_token0"], a["page_table"] = \
+        blob_ptrs, n_tokens, levels, dst_token0, page_table_ptrs
+    a["orig_tokens"], a["sink"], a["window"], a["compact"] = orig_tokens, sinks, windows, compact
+    return torch.from_numpy(a.view(np.uint8).copy()).to(device)
+
+
+def encode_kept_batch(items: torch.Tensor, n_items: int, max_kept_tokens_per_item: int, k: torch.Tensor,
+                      v: torch.Tensor, stream=None) -> None:
+    """kvh_encode_kept_batch: all items in one launch; `items` comes from make_kept_enc_items."""
+    view, dt = _view(k, v)
+    _require_cuda(items)
+    l, _, c = k.shape
+    _check(lib().kvh_encode_kept_batch(items.data_ptr(), n_items, max_kept_tokens_per_item, dt, l, c,
+                                       ctypes.byref(view), _stream_ptr(stream)), "kvh_encode_kept_batch")
+
+
+def decode_kept_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, k_dst: torch.Tensor,
+                      v_dst: torch.Tensor, paged: bool = False, block_tokens: int = 16,
+                      status: torch.Tensor | None = None, stream=None) -> None:
+    """kvh_decode_kept_batch: ordinary and token-dropped blobs in one launch; `items` from make_kept_items."""
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(items, status)
+    if status is not None and (status.dtype != torch.int32 or status.numel() < n_items):
+        raise ValueError("status must be int32 with one entry per item")
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_decode_kept_batch(items.data_ptr(), n_items, max_tokens_per_item, dt, l, c, ctypes.byref(view),
+                                       block_tokens, status.data_ptr() if status is not None else None,
+                                       _stream_ptr(stream)), "kvh_decode_kept_batch")
+
+
 def _dt_code(dtype) -> int:
     if dtype in _TORCH_DT:
         return _TORCH_DT[dtype]
@@ -348,8 +400,10 @@ class Loader:
         return lib().kvh_loader_slot_bytes(self._h)
 
     def run(self, host_blobs, n_tokens, levels, dst_token0, k_dst: torch.Tensor, v_dst: torch.Tensor,
-            page_tables=None, block_tokens: int = 16, status: torch.Tensor | None = None, stream=None) -> None:
-        """kvh_loader_run over pinned uint8 host tensors `host_blobs`; page_tables: int32 device tensors or None."""
+            page_tables=None, block_tokens: int = 16, status: torch.Tensor | None = None, stream=None,
+            drops=None) -> None:
+        """kvh_loader_run over pinned uint8 host tensors `host_blobs`; page_tables: int32 device tensors or None;
+        drops: per blob None (ordinary) or (orig_tokens, sink, window, compact) for a token-dropped one."""
         paged = page_tables is not None
         view, dt = _view(k_dst, v_dst, paged)
         _require_cuda(status)
@@ -362,6 +416,10 @@ class Loader:
         a = np.zeros(n, dtype=LOAD_ITEM)
         a["blob_host"] = [b.data_ptr() for b in host_blobs]
         a["n_tokens"], a["level"], a["dst_token0"] = n_tokens, levels, dst_token0
+        if drops is not None:
+            for i, d in enumerate(drops):
+                if d is not None:
+                    a["orig_tokens"][i], a["sink"][i], a["window"][i], a["compact"][i] = d[0], d[1], d[2], int(d[3])
         if paged:
             for t in page_tables:
                 _require_cuda(t)

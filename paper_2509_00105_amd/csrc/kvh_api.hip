@@ -265,6 +265,44 @@ int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_token
   return launch_transcode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
 }
 
+int kvh_encode_kept_batch(const kvh_kept_enc_item* items_dev, int n_items, int max_kept_tokens_per_item, kvh_dtype dt,
+                          int l, int c, const kvh_kv_view* src, void* stream) {
+  if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
+  if (int rc = check_view(src)) return rc;
+  if (int rc = check_shape(l, max_kept_tokens_per_item, c)) return rc;
+  EncodeParams a{};
+  a.kept_items = items_dev;
+  a.k = static_cast<const uint16_t*>(src->k);
+  a.v = static_cast<const uint16_t*>(src->v);
+  a.layer_stride = src->layer_stride;
+  a.token_stride = src->token_stride;
+  a.l = l;
+  a.c = c;
+  a.split = kNoSplit;
+  return launch_encode(a, dt, n_items, max_kept_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
+int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l,
+                          int c, const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream) {
+  if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16) ||
+      block_tokens < 1)
+    return KVH_E_ARG;
+  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
+  DecodeParams a{};
+  a.kept_items = items_dev;
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.status = status_dev;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = block_tokens;
+  a.split = kNoSplit;
+  return launch_decode(a, dt, n_items, max_tokens_per_item, static_cast<hipStream_t>(stream));
+}
+
 int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream) {
   if (dst_dev == nullptr || src_dev == nullptr || bytes == 0) return KVH_E_ARG;
   if (bytes % 16 != 0 || !aligned16(dst_dev) || !aligned16(src_dev)) return KVH_E_ALIGN;

@@ -103,6 +103,7 @@ __device__ __forceinline__ float encode_inv(float mn, float mx) {
 // ---- kernel parameter blocks and launchers (defined next to their kernels) -----------------------
 struct DecodeParams {
   const kvh_item* items;  // device array of jobs, or nullptr: decode `one`
+  const kvh_kept_item* kept_items;  // device array of jobs that may be token-dropped (then `items` is nullptr)
   kvh_item one;
   uint16_t* k;
   uint16_t* v;
@@ -118,6 +119,7 @@ struct DecodeParams {
 
 struct EncodeParams {
   const kvh_enc_item* items;  // device array of jobs, or nullptr: encode `one`
+  const kvh_kept_enc_item* kept_items;  // device array of token-dropping jobs (then `items` is nullptr)
   kvh_enc_item one;
   const uint16_t* k;
   const uint16_t* v;
@@ -131,6 +133,14 @@ struct EncodeParams {
 };
 
 constexpr int32_t kNoSplit = 0x7fffffff;
+
+// Token dropping as the kernels see it: kept token t >= split sits `jump` rows further on in the full
+// entry; the three header words are what the blob records (all zero for an ordinary blob).
+struct DropInfo {
+  int32_t split;
+  int64_t jump;
+  uint32_t orig_tokens, sink, window;
+};
 
 struct TranscodeParams {
   const kvh_tc_item* items;  // device array of jobs, or nullptr: transcode `one`

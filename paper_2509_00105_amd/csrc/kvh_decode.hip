@@ -162,7 +162,7 @@ __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int
 // blob pointer, so these loads stay inside the buffer whatever the header says.
 template <int DT, int BITS>
 __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
-                                            int t0, int span, float* kshare, int t0_block) {
+                                            int t0, int span, float* kshare, int t0_block, const DropInfo& drop) {
   const int lane = threadIdx.x & (kWave - 1);
   const int n = it.n_tokens;
   const int c = a.c;
@@ -185,8 +185,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   int32_t my_row = 0;
   {
     int t = t0 + (lane & (kDecRows - 1));
-    const bool batch = a.items != nullptr;  // batch items are never token-dropped entries
-    const int64_t hop = (!batch && t >= a.split) ? a.jump : 0;
+    const int64_t hop = t >= drop.split ? drop.jump : 0;
     if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
   }
 
@@ -222,9 +221,8 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     for (int s = 0; s < kDecSegs; ++s) cw[i][s].load(codes + (size_t)t * geo.row_bytes + ch[s] * BITS / 8);
   }
 
-  const bool plain = a.items != nullptr;
-  if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes(),
-                      plain ? 0u : a.hdr_orig_tokens, plain ? 0u : a.hdr_sink, plain ? 0u : a.hdr_window)) {
+  if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes(), drop.orig_tokens,
+                      drop.sink, drop.window)) {
     if (a.status != nullptr && lane == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
     return;
   }
@@ -310,6 +308,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
   const int lay_kv = blockIdx.y;
   kvh_item it;
+  DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
+  bool consistent = true;
   if (a.items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
     uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16);
@@ -318,8 +318,33 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
     it.level = (int32_t)lo.w;
     it.dst_token0 = (int64_t)((uint64_t)hi.x | (uint64_t)hi.y << 32);
     it.page_table = reinterpret_cast<const int32_t*>((uint64_t)hi.z | (uint64_t)hi.w << 32);
+  } else if (a.kept_items != nullptr) {
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(a.kept_items + item_idx);
+    uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16), ex = gload<uintx4>(p + 32);
+    it.blob = reinterpret_cast<const void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
+    it.n_tokens = (int32_t)lo.z;
+    it.level = (int32_t)lo.w;
+    it.dst_token0 = (int64_t)((uint64_t)hi.x | (uint64_t)hi.y << 32);
+    it.page_table = reinterpret_cast<const int32_t*>((uint64_t)hi.z | (uint64_t)hi.w << 32);
+    const uint32_t orig = (uint32_t)uniform((int32_t)ex.x), sink = (uint32_t)uniform((int32_t)ex.y),
+                   window = (uint32_t)uniform((int32_t)ex.z);
+    const bool compact = uniform((int32_t)ex.w) != 0;
+    if ((orig | sink | window) != 0) {
+      const uint64_t sw = (uint64_t)sink + window;
+      const uint32_t kept = sw >= orig ? orig : (uint32_t)sw;
+      consistent = orig <= 0x7fffffffu && sink <= 0x7fffffffu && window <= 0x7fffffffu && kept >= 1 &&
+                   kept == (uint32_t)uniform(it.n_tokens);
+      drop.orig_tokens = orig;
+      drop.sink = sink;
+      drop.window = window;
+      if (consistent && kept < orig && !compact) {
+        drop.split = (int32_t)sink;
+        drop.jump = (int64_t)orig - window - sink;
+      }
+    }
   } else {
     it = a.one;
+    drop = DropInfo{a.split, a.jump, a.hdr_orig_tokens, a.hdr_sink, a.hdr_window};
   }
   it.blob = uniform(it.blob);
   it.n_tokens = uniform(it.n_tokens);
@@ -335,10 +360,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   if (it.n_tokens < 1 || t0_block >= it.n_tokens) return;  // block-uniform
   const int lam = lay_kv >> 1;
   const bool is_v = lay_kv & 1;
-  switch (it.level) {
-    case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
-    case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
-    case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block); break;
+  switch (consistent ? it.level : -1) {
+    case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
+    case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
+    case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
     default:
       if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
       break;

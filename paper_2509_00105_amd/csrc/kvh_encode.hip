@@ -294,6 +294,7 @@ template <int DT>
 __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void encode_kernel(EncodeParams a) {
   __shared__ float red[2 * kEncWaves * kStripCh];  // 32 KiB
   kvh_enc_item it;
+  DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
   if (a.items != nullptr) {
     const kvh_enc_item* p = a.items + blockIdx.z;
     uintx4 lo = gload<uintx4>(p);
@@ -302,15 +303,33 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
     it.src_token0 = (int64_t)((uint64_t)lo.z | (uint64_t)lo.w << 32);
     it.n_tokens = (int32_t)hi.x;
     it.level = (int32_t)hi.y;
+  } else if (a.kept_items != nullptr) {
+    const kvh_kept_enc_item* p = a.kept_items + blockIdx.z;
+    uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(reinterpret_cast<const uint8_t*>(p) + 16);
+    it.blob = reinterpret_cast<void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
+    it.src_token0 = (int64_t)((uint64_t)lo.z | (uint64_t)lo.w << 32);
+    const int32_t orig = uniform((int32_t)hi.x), sink = uniform((int32_t)hi.y), window = uniform((int32_t)hi.z);
+    it.level = (int32_t)hi.w;
+    const bool ok = orig >= 1 && sink >= 0 && window >= 0 && (int64_t)sink + window >= 1;
+    const int64_t sw = (int64_t)sink + window;
+    it.n_tokens = ok ? (int32_t)(sw >= orig ? orig : sw) : 0;  // nothing kept: the item is skipped below
+    drop.orig_tokens = (uint32_t)orig;
+    drop.sink = (uint32_t)sink;
+    drop.window = (uint32_t)window;
+    if (ok && sw < orig) {
+      drop.split = sink;
+      drop.jump = (int64_t)orig - window - sink;
+    }
   } else {
     it = a.one;
+    drop = DropInfo{a.split, a.jump, a.hdr_orig_tokens, a.hdr_sink, a.hdr_window};
   }
   it.blob = uniform(it.blob);
   it.src_token0 = uniform(it.src_token0);
   it.n_tokens = uniform(it.n_tokens);
   it.level = uniform(it.level);
-  const int split = a.items != nullptr ? kNoSplit : a.split;  // batch items are never token-dropped entries
-  const int64_t jump = a.items != nullptr ? 0 : a.jump;
+  const int split = drop.split;
+  const int64_t jump = drop.jump;
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
   const int tile = blockIdx.x / nstrips;
   const int strip = blockIdx.x - tile * nstrips;
@@ -333,9 +352,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
       case 5: w = (uint32_t)kGroup | (uint32_t)kGroup << 16; break;
       case 6: w = (uint32_t)total; break;
       case 7: w = (uint32_t)(total >> 32); break;
-      case 8: w = a.items != nullptr ? 0u : a.hdr_orig_tokens; break;
-      case 9: w = a.items != nullptr ? 0u : a.hdr_sink; break;
-      case 10: w = a.items != nullptr ? 0u : a.hdr_window; break;
+      case 8: w = drop.orig_tokens; break;
+      case 9: w = drop.sink; break;
+      case 10: w = drop.window; break;
       default: break;
     }
     gstore<uint32_t>(blob + 4 * threadIdx.x, w);

@@ -18,7 +18,7 @@ namespace {
 
 constexpr int kMaxSlots = 64;
 constexpr int kMaxGroup = 32;                                   // blobs per group
-constexpr size_t kDescBytes = (size_t)kMaxGroup * sizeof(kvh_item);  // descriptor area at the head of a slot
+constexpr size_t kDescBytes = (size_t)kMaxGroup * sizeof(kvh_kept_item);  // descriptor area at the head of a slot
 #ifndef KVH_LD_BLOCKS
 #define KVH_LD_BLOCKS 4   // copy blocks per blob (the bus, not the CUs, bounds the copy: few blocks leave the rest to the decode)
 #endif
@@ -36,7 +36,7 @@ struct CopyGroup {
   const uint8_t* src[kMaxGroup];  // pinned host memory, device-visible
   uint64_t off[kMaxGroup];        // byte offset of the blob inside the slot
   uint64_t n16[kMaxGroup];        // blob size in 16-byte words
-  kvh_item item[kMaxGroup];       // decode descriptor (blob = slot + off)
+  kvh_kept_item item[kMaxGroup];  // decode descriptor (blob = slot + off)
 };
 
 // grid = (kCopyBlocksPerBlob, blobs of the group)
@@ -45,9 +45,9 @@ __global__ __launch_bounds__(kCopyThreads) void load_group_kernel(CopyGroup g, u
   const uintx4* src = reinterpret_cast<const uintx4*>(g.src[j]);
   uintx4* dst = reinterpret_cast<uintx4*>(slot + g.off[j]);
   const uint64_t n16 = g.n16[j];
-  if (blockIdx.x == 0 && threadIdx.x < sizeof(kvh_item) / 4) {
+  if (blockIdx.x == 0 && threadIdx.x < sizeof(kvh_kept_item) / 4) {
     const uint32_t* d = reinterpret_cast<const uint32_t*>(&g.item[j]);
-    reinterpret_cast<uint32_t*>(slot)[j * (sizeof(kvh_item) / 4) + threadIdx.x] = d[threadIdx.x];
+    reinterpret_cast<uint32_t*>(slot)[j * (sizeof(kvh_kept_item) / 4) + threadIdx.x] = d[threadIdx.x];
   }
   const uint64_t stride = (uint64_t)gridDim.x * kCopyThreads;
   for (uint64_t i = (uint64_t)blockIdx.x * kCopyThreads + threadIdx.x; i < n16; i += stride * kCopyUnroll) {
@@ -167,7 +167,11 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
         return KVH_E_ARG;
       }
     }
-    if (it.dst_token0 + it.n_tokens > INT32_MAX) return KVH_E_ARG;
+    if ((it.orig_tokens | it.sink | it.window) != 0) {  // a token-dropped blob: n_tokens is what is kept
+      if (kvh_kept_tokens(it.orig_tokens, it.sink, it.window) != it.n_tokens) return KVH_E_SHAPE;
+    }
+    const int64_t span = (it.orig_tokens > it.n_tokens && !it.compact) ? it.orig_tokens : it.n_tokens;
+    if (it.dst_token0 + span > INT32_MAX) return KVH_E_ARG;
   }
   hipStream_t compute = static_cast<hipStream_t>(stream);
   DecodeParams a{};
@@ -194,7 +198,8 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
       g.src[g.n] = static_cast<const uint8_t*>(it.blob_host);
       g.off[g.n] = kDescBytes + used;
       g.n16[g.n] = bytes / 16;
-      g.item[g.n] = kvh_item{slot + kDescBytes + used, it.n_tokens, it.level, it.dst_token0, it.page_table};
+      g.item[g.n] = kvh_kept_item{slot + kDescBytes + used, it.n_tokens, it.level, it.dst_token0, it.page_table,
+                                  it.orig_tokens, it.sink, it.window, it.compact};
       if (it.n_tokens > max_tokens) max_tokens = it.n_tokens;
       used += bytes;
       ++g.n;
@@ -206,7 +211,7 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
     KVH_HIP_CHECK_LAUNCH();
     if (hipEventRecord(ld->copied[s], ld->copy_stream) != hipSuccess) return KVH_E_HIP;
     if (hipStreamWaitEvent(compute, ld->copied[s], 0) != hipSuccess) return KVH_E_HIP;
-    a.items = reinterpret_cast<const kvh_item*>(slot);
+    a.kept_items = reinterpret_cast<const kvh_kept_item*>(slot);
     a.status = status_dev != nullptr ? status_dev + first : nullptr;
     if (int rc = launch_decode(a, dt, g.n, max_tokens, compute)) return rc;
     if (hipEventRecord(ld->freed[s], compute) != hipSuccess) return KVH_E_HIP;

@@ -37,7 +37,8 @@ def test_every_declared_symbol_is_exported(lib):
                           "kvh_blob_size", "kvh_level_bits", "kvh_num_levels", "kvh_strerror", "kvh_copy_probe",
                           "kvh_kept_tokens", "kvh_encode_kept", "kvh_decode_kept", "kvh_transcode", "kvh_transcode_batch",
                           "kvh_loader_create", "kvh_loader_run", "kvh_loader_destroy", "kvh_loader_slot_bytes",
-                          "kvh_policy_plan", "kvh_policy_utility", "kvh_policy_marginal_utility_drop"}
+                          "kvh_policy_plan", "kvh_policy_utility", "kvh_policy_marginal_utility_drop",
+                          "kvh_encode_kept_batch", "kvh_decode_kept_batch"}
     for n in names:
         assert hasattr(lib, n), n
 
@@ -126,6 +127,11 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert kept_d(P, 0, 1, 256, 1024, 0, 0, 0, v, 0, 0, None, 16, None, None) == E_SHAPE
     assert kept_d(P, 0, 1, 256, 1024, 4, 60, 0, v, 0, 0, P, 0, None, None) == E_ARG
     assert kept_d(P, 0, 1, 256, 1024, 4, 60, 0, v, 2**31 - 100, 0, None, 16, None, None) == E_ARG
+
+    assert lib.kvh_encode_kept_batch(None, 1, 256, 0, 1, 1024, v, None) == E_ARG
+    assert lib.kvh_encode_kept_batch(P, 1, 256, 0, 1, 1000, v, None) == E_SHAPE
+    assert lib.kvh_decode_kept_batch(P, 0, 256, 0, 1, 1024, v, 16, None, None) == E_ARG
+    assert lib.kvh_decode_kept_batch(P, 1, 256, 0, 1, 1024, v, 0, None, None) == E_ARG
 
     tc = lib.kvh_transcode
     Q = P + (1 << 30)

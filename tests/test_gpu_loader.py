@@ -51,9 +51,9 @@ def test_pipelined_load_matches_oracle(kvh, n_slots, dt):
     blobs, t0s, want_k, want_v, N = make_entries(dt, l, c, lens, levels, seed=60 + n_slots)
     slot = max(b.numel() for b in blobs)
     # slots that hold the largest blob plus the descriptor area: groups of one to a few blobs, several ring turns
-    staging = torch.empty(n_slots * (slot + 1024), dtype=torch.uint8, device="cuda")
+    staging = torch.empty(n_slots * (slot + 1536), dtype=torch.uint8, device="cuda")
     ld = kvh.Loader(staging, n_slots)
-    assert slot <= ld.slot_bytes < slot + 1024
+    assert slot <= ld.slot_bytes < slot + 1536
     ok = torch.full((l, N, c), 3.0, dtype=TDT[dt], device="cuda"); ov = torch.full_like(ok, 3.0)
     status = torch.zeros(len(lens), dtype=torch.int32, device="cuda")
     ld.run(blobs, lens, levels, t0s, ok, ov, status=status)
@@ -79,7 +79,7 @@ def test_pipelined_load_paged_and_header_mismatch(kvh):
         assert oracle.decode_into(b.numpy(), dt, l, n, c, lv, pk, pv, dst_token0=t0, page_table=table, block_tokens=bt) == 0
     gk = torch.zeros((l, P + 3, bt, c), dtype=torch.bfloat16, device="cuda"); gv = torch.zeros_like(gk)
     tab = torch.from_numpy(table).cuda()
-    staging = torch.empty(2 * (max(b.numel() for b in blobs) + 1024), dtype=torch.uint8, device="cuda")
+    staging = torch.empty(2 * (max(b.numel() for b in blobs) + 1536), dtype=torch.uint8, device="cuda")
     ld = kvh.Loader(staging, 2)
     status = torch.zeros(3, dtype=torch.int32, device="cuda")
     ld.run(blobs, lens, levels, t0s, gk, gv, page_tables=[tab] * 3, block_tokens=bt, status=status)
@@ -155,3 +155,29 @@ def test_store_path_encode_straight_into_pinned_host_memory(kvh):
     kvh.transcode(dev_blob, torch.bfloat16, l, lens[1], c, 0, 2, out=low)
     torch.cuda.synchronize()
     assert np.array_equal(low.numpy(), oracle.transcode(got[offs[1]:offs[1] + sizes[1]], dt, l, lens[1], c, 0, 2))
+
+
+def test_loader_takes_token_dropped_blobs(kvh):
+    """Ordinary and token-dropped blobs mixed in one run of the loader."""
+    dt, l, c = F16, 2, 256
+    N, sink, window = 400, 16, 150
+    k, v = gen.make_kv(l, N + 256, c, dt, seed=91)
+    kept_blob = oracle.encode_kept(np.ascontiguousarray(k[:, :N]), np.ascontiguousarray(v[:, :N]), dt, sink, window, 2)
+    plain_blob = oracle.encode(np.ascontiguousarray(k[:, N:]), np.ascontiguousarray(v[:, N:]), dt, 0)
+    n_kept = oracle.kept_tokens(N, sink, window)
+    wk = np.full((l, N + 256, c), 0x2222, np.uint16); wv = wk.copy()
+    assert oracle.decode_kept_into(kept_blob, dt, l, N, c, sink, window, 2, wk, wv) == 0
+    assert oracle.decode_into(plain_blob, dt, l, 256, c, 0, wk, wv, dst_token0=N) == 0
+    gk = torch.from_numpy(np.full((l, N + 256, c), 0x2222, np.uint16).view(np.int16)).cuda().view(torch.float16)
+    gv = gk.clone()
+    blobs = [torch.from_numpy(kept_blob).pin_memory(), torch.from_numpy(plain_blob).pin_memory()]
+    staging = torch.empty(2 * (max(b.numel() for b in blobs) + 1536), dtype=torch.uint8, device="cuda")
+    ld = kvh.Loader(staging, 2)
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    ld.run(blobs, [n_kept, 256], [2, 0], [0, N], gk, gv, status=status, drops=[(N, sink, window, False), None])
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    assert np.array_equal(to_host(gk), wk) and np.array_equal(to_host(gv), wv)
+    with pytest.raises(kvh.KVHError):  # n_tokens that is not what the drop words keep
+        ld.run(blobs[:1], [n_kept - 1], [2], [0], gk, gv, drops=[(N, sink, window, False)])
+    ld.close()

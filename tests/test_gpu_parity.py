@@ -321,3 +321,56 @@ def test_token_dropping_paged_and_header_checks(kvh):
     kvh.decode_kept(plain, level, N, sink, window, ok, ov, status=status)
     torch.cuda.synchronize()
     assert status.item() == 1 and bool((ok == 3.0).all())
+
+
+def test_token_dropping_batched_with_ordinary_items(kvh):
+    """kvh_encode_kept_batch / kvh_decode_kept_batch: several entries with their own (N, sink, window) in one launch,
+    an ordinary blob among the decode items, one compact item, one inconsistent item."""
+    dt, l, c = BF16, 2, 256
+    entries = [(300, 4, 124, 2), (515, 128, 200, 0), (130, 1, 1, 1), (64, 100, 100, 2), (257, 0, 129, 1)]  # N, sink, window, level
+    starts = np.concatenate([[0], np.cumsum([e[0] for e in entries])[:-1]])
+    total = int(sum(e[0] for e in entries))
+    k, v = gen.make_kv(l, total, c, dt, seed=77)
+    kd, vd = to_dev(k, dt), to_dev(v, dt)
+    kept = [oracle.kept_tokens(N, s, w) for N, s, w, _ in entries]
+    sizes = [kvh.blob_size(l, n, c, lv) for n, (_, _, _, lv) in zip(kept, entries)]
+    offs = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    blobs = torch.zeros(int(sum(sizes)), dtype=torch.uint8, device="cuda")
+    ptrs = [blobs.data_ptr() + int(o) for o in offs]
+    items = kvh.make_kept_enc_items(ptrs, starts, [e[0] for e in entries], [e[1] for e in entries], [e[2] for e in entries],
+                                    [e[3] for e in entries], "cuda")
+    kvh.encode_kept_batch(items, len(entries), max(kept), kd, vd)
+    torch.cuda.synchronize()
+    got = blobs.cpu().numpy()
+    wants = []
+    for (N, s, w, lv), t0, o, sz in zip(entries, starts, offs, sizes):
+        want = oracle.encode_kept(np.ascontiguousarray(k[:, t0:t0 + N]), np.ascontiguousarray(v[:, t0:t0 + N]), dt, s, w, lv)
+        assert_same_blob(got[o:o + sz], want, "kept entry at %d" % t0)
+        wants.append(want)
+
+    # decode: entries 0..3 back to their places, entry 4 compact behind them, plus an ordinary blob and a bad item
+    plain_k, plain_v = gen.make_kv(l, 200, c, dt, seed=78)
+    plain = oracle.encode(plain_k, plain_v, dt, 1)
+    plain_dev = torch.from_numpy(plain).cuda()
+    rows = total + 200 + kept[4]
+    wk = np.full((l, rows, c), 0x1111, np.uint16); wv = wk.copy()
+    ok = to_dev(wk.copy(), dt); ov = to_dev(wv.copy(), dt)
+    d_ptrs, d_n, d_lv, d_t0, d_orig, d_sink, d_win, d_comp = [], [], [], [], [], [], [], []
+    for i, ((N, s, w, lv), t0) in enumerate(zip(entries, starts)):
+        compact = i == 4
+        dst = total + 200 if compact else int(t0)
+        assert oracle.decode_kept_into(wants[i], dt, l, N, c, s, w, lv, wk, wv, dst_token0=dst, compact=compact) == 0
+        d_ptrs.append(ptrs[i]); d_n.append(kept[i]); d_lv.append(lv); d_t0.append(dst)
+        d_orig.append(N); d_sink.append(s); d_win.append(w); d_comp.append(int(compact))
+    assert oracle.decode_into(plain, dt, l, 200, c, 1, wk, wv, dst_token0=total) == 0
+    d_ptrs.append(plain_dev.data_ptr()); d_n.append(200); d_lv.append(1); d_t0.append(total)
+    d_orig.append(0); d_sink.append(0); d_win.append(0); d_comp.append(0)
+    # a seventh item whose n_tokens is not what (N, sink, window) keep: status 1, nothing written
+    d_ptrs.append(ptrs[0]); d_n.append(kept[0] - 1); d_lv.append(entries[0][3]); d_t0.append(0)
+    d_orig.append(entries[0][0]); d_sink.append(entries[0][1]); d_win.append(entries[0][2]); d_comp.append(0)
+    ditems = kvh.make_kept_items(d_ptrs, d_n, d_lv, d_t0, [0] * 7, d_orig, d_sink, d_win, d_comp, "cuda")
+    status = torch.zeros(7, dtype=torch.int32, device="cuda")
+    kvh.decode_kept_batch(ditems, 7, max(d_n), ok, ov, status=status)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0] * 6 + [1]
+    assert_same_bits(to_host(ok), wk, dt, "K"); assert_same_bits(to_host(ov), wv, dt, "V")

@@ -267,7 +267,7 @@ def test_config2_transcode_token_dropping_and_load_path_at_full_size(kvh):
     plain = decode_all(kvh, src, spans, levels, offs, chunk, torch.zeros_like(kv))
     host_all = torch.empty(src.numel(), dtype=torch.uint8).pin_memory()
     host_all.copy_(src)
-    staging = torch.empty(2 * (4 * size + 1024), dtype=torch.uint8, device="cuda")
+    staging = torch.empty(2 * (4 * size + 1536), dtype=torch.uint8, device="cuda")
     ld = kvh.Loader(staging, 2)
     piped = torch.zeros_like(kv)
     status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
