@@ -11,6 +11,12 @@ from oracle import policy_ref as P
 
 @pytest.fixture(scope="module")
 def kvh():
+    import os
+
+    from paper_2509_00105_amd import build
+
+    if not os.path.exists(build.LIB):  # host-only code: compiling it needs no GPU
+        build.build()
     import paper_2509_00105_amd as m
 
     m.lib()
