@@ -163,7 +163,7 @@ def main():
             del err
         torch.cuda.synchronize()
 
-    # Outside the timed region: what one chunk costs on its own (the "decompression overhead" the paper's
+    # Outside the timed region: what one chunk costs on its own (the cost of decompression that the paper's
     # estimator profiles per entry): kvh_decode / kvh_encode of a single 256-token chunk, 100 calls back to back.
     single = []
     with torch.cuda.stream(stream):

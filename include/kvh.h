@@ -2,12 +2,12 @@
  * kvh.h — C ABI of the MI355X KV-cache level codec.
  *
  * The operations are the two compute steps of the AdaptCache executor (Design section: the
- * executor "implements the compression decisions"; the estimator profiles the "decompression
- * overhead"): compress a KV-cache entry with the quantisation method at a chosen rate, and
+ * executor carries out the compression decisions; the estimator profiles what decompression
+ * costs): compress a KV-cache entry with the quantisation method at a chosen rate, and
  * decompress a stored entry when it is loaded for reuse.  A KV-cache entry is a tensor of
  * l layers x N tokens x c channels for each of K and V (the paper's NumLayers, NumTokens,
  * NumChannels) stored at a quality level k (its Level); the only rate the paper names is
- * "2 bits" (Preliminary Results).  The paper fixes no equations or formats for the codec; the
+ * two bits per value (Preliminary Results).  The paper fixes no equations or formats for the codec; the
  * concrete definition implemented here is:
  *
  *   level 0/1/2 -> b = 8/4/2 bits per element, L = 2^b - 1
@@ -66,7 +66,7 @@ typedef enum {
 /* Value written to *status_dev by a decode kernel whose blob header disagrees with the call. */
 #define KVH_DEV_HEADER_MISMATCH 1
 
-/* The level table (reading of the paper's Level k / "compression rate"): 3 levels. */
+/* The level table (reading of the paper's Level k, its compression rate): 3 levels. */
 int kvh_num_levels(void);
 /* Bits per element of a level: 0,1,2 -> 8,4,2; anything else -> -1. */
 int kvh_level_bits(int level);
@@ -145,8 +145,8 @@ int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_
                      const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
 
 /* ---- Token dropping ------------------------------------------------------------------------------
- * The paper's second compression method: some contexts "are only important at the beginning and the
- * end (which is suitable for token dropping)" (Introduction); the evaluation's fixed-rate
+ * The paper's second compression method: for contexts that matter mostly at their beginning and their
+ * end, dropping the tokens in between suits (Introduction); the evaluation's fixed-rate
  * token-dropping baseline (Preliminary Results).  The paper defines nothing further; here an entry of N
  * tokens keeps its first `sink` and last `window` tokens (all of them if sink + window >= N) and the
  * kept tokens, in order, are stored as an ordinary blob of n = kvh_kept_tokens(N, sink, window) tokens
@@ -206,7 +206,7 @@ int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_t
                           int c, const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
 
 /* ---- Transcode ------------------------------------------------------------------------------------
- * The paper's policy lowers the quality of stored entries step by step ("compress furthermore" from
+ * The paper's policy lowers the quality of stored entries step by step (a further compression from
  * rate m to rate n; Design section, marginal utility drop).  kvh_transcode re-compresses a stored blob
  * from level_in to level_out in one kernel, without materialising 16-bit KV: the output is, byte for
  * byte, what kvh_encode would produce from the tensors kvh_decode writes for the source blob.

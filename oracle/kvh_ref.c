@@ -1,11 +1,11 @@
 /*
  * kvh_ref.c — CPU ORACLE of the KV-cache level codec.  TEST INFRASTRUCTURE ONLY.
  *
- * Plain, slow, scalar C that states what "compress a KV-cache entry with the quantisation
- * method at a rate" and "decompress it on load" compute (AdaptCache: Introduction — lossy KV
+ * Plain, slow, scalar C that states what compressing a KV-cache entry with the quantisation
+ * method at a rate, and decompressing it on load, compute (AdaptCache: Introduction — lossy KV
  * compression by quantisation; Design — the executor applies the chosen method/rate, the
  * estimator profiles the decompression overhead; Preliminary Results — the quantiser is the
- * cited per-channel-K / per-token-V min-max quantiser, named rate "2 bits").  The paper gives
+ * cited per-channel-K / per-token-V min-max quantiser, named rate: two bits).  The paper gives
  * no equations for the codec; every concrete choice below is a stated reading, listed in the
  * design notes of this repository, and pinned by the CPU tests (worked examples, closed
  * forms, invariants, brute force in exact arithmetic, conversions checked exhaustively

@@ -1,6 +1,6 @@
 // Level decoder: unpack b-bit codes, dequantise with the stored (min, max) of each group and
-// write fp16/bf16 KV rows, contiguous or through a page table (the "decompression" whose
-// overhead the paper's estimator profiles; Design section).
+// write fp16/bf16 KV rows, contiguous or through a page table (the decompression whose
+// cost the paper's estimator profiles; Design section).
 //
 // Streaming kernel.  The unit of work is one wave decoding 8 consecutive token rows of a
 // 1024-channel span (two 512-channel segments), i.e. 16 KiB of contiguous output when c = 1024.

@@ -1,5 +1,5 @@
 // Level encoder: per-group min/max, quantise to b bits, bit-pack and write the blob
-// ("compress a KV-cache entry with the quantisation method at a rate"; Design section, and
+// (compression of a KV-cache entry with the quantisation method at a rate; Design section, and
 // the per-channel-K / per-token-V quantiser named in Preliminary Results).  Single pass: each
 // input element is read from HBM once.
 //   K (statistics over 128 tokens of a channel): a block owns one token-group x one 512-channel

@@ -1,5 +1,5 @@
 // Level transcoder: re-compress a stored blob from b_in to b_out bits per element without ever
-// writing 16-bit KV to memory (the policy's "compress an entry further" step; Design section,
+// writing 16-bit KV to memory (the policy's step that compresses a stored entry further; Design section,
 // marginal utility drop).  The result is, byte for byte, encode(decode(blob)).
 //
 // Why no statistics pass is needed: in a blob written by the encoder (or by this kernel) every

@@ -1,6 +1,6 @@
 """CPU-only pins of the oracle (oracle/kvh_ref.c) against things other than itself.
 
-The paper (AdaptCache) names its quantisation method and the rate "2 bits" (Preliminary
+The paper (AdaptCache) names its quantisation method and one rate, two bits (Preliminary
 Results) but prints no equations, examples or error figures for it, so the pins are: the
 hand-computed worked examples under tests/golden/, exact-arithmetic brute force, closed forms
 (uniform-quantiser RMS = step / sqrt(12), blob-size closed form), invariants (step-bounded

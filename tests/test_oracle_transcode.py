@@ -1,5 +1,5 @@
 """CPU-only pins of the oracle's transcode (re-compress a stored entry from rate m to rate n, the step the
-paper's greedy policy takes when it "compresses further"; Design section, marginal utility drop).  The
+paper's greedy policy takes when it lowers an entry's rate; Design section, marginal utility drop).  The
 oracle is decode followed by encode.  Pins that do not re-run that composition: a hand-computed ramp, the
 statistics that must survive (a group always holds code 0 and code L, which decode to the stored min and
 max exactly), the identity m -> m, closeness to a direct encode at the target level, the error bound,
