@@ -91,3 +91,22 @@ def test_many_layers_one_token_and_wide_channels(kvh, dt):
             wk, wv = oracle.decode(want, dt, l, n, c, level)
             assert np.array_equal(to_host(ok), wk) and np.array_equal(to_host(ov), wv), (l, n, c, level)
             assert np.array_equal(low.cpu().numpy(), oracle.transcode(want, dt, l, n, c, level, 2)), (l, n, c, level)
+
+
+def test_one_long_entry_in_a_single_blob(kvh):
+    """40,003 tokens in ONE blob (313 K token-groups, the last one ragged): a long grid in x, 64-bit section offsets."""
+    dt, l, n, c, level = F16, 1, 40003, 1024, 2
+    k, v = gen.make_kv(l, n, c, dt, seed=4)
+    want = oracle.encode(k, v, dt, level)
+    blob = kvh.encode(to_dev(k, dt), to_dev(v, dt), level)
+    torch.cuda.synchronize()
+    assert np.array_equal(blob.cpu().numpy(), want)
+    ok = torch.zeros((l, n, c), dtype=TDT[dt], device="cuda"); ov = torch.zeros_like(ok)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kvh.decode(blob, level, n, ok, ov, status=status)
+    low = kvh.transcode(kvh.encode(to_dev(k, dt), to_dev(v, dt), 1), dt, l, n, c, 1, 2, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    wk, wv = oracle.decode(want, dt, l, n, c, level)
+    assert np.array_equal(to_host(ok), wk) and np.array_equal(to_host(ov), wv)
+    assert np.array_equal(low.cpu().numpy(), oracle.transcode(oracle.encode(k, v, dt, 1), dt, l, n, c, 1, 2))
