@@ -75,15 +75,22 @@ def cpu_baseline(kv_host_chunks, dt, l, chunk, c, gpu_blobs):
         oracle.decode(blob, dt, l, chunk, c, level)
         return ci, level, blob
 
+    unc_bytes = 2 * l * chunk * c * 2
+    # one thread first: the first sampled chunk at each level, encode + decode
+    t0 = time.perf_counter()
+    for level in range(3):
+        job((0, level))
+    single_gbps = 3 * 2 * unc_bytes / (time.perf_counter() - t0) / 1e9
+
     tasks = [(ci, level) for level in range(3) for ci in range(len(kv_host_chunks))]
     t0 = time.perf_counter()
     with cf.ThreadPoolExecutor(max_workers=cores) as ex:
         results = list(ex.map(job, tasks))
     wall = time.perf_counter() - t0
-    unc_bytes = 2 * l * chunk * c * 2
     total = unc_bytes * 2 * len(tasks)  # encode + decode of every (chunk, level)
     parity = all(np.array_equal(blob, gpu_blobs[(ci, level)]) for ci, level, blob in results)
     return {"value": total / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "single_thread_GBps": single_gbps,
             "sample": "%d of the workload's 256-token chunks (%d MiB uncompressed), encode+decode at 8/4/2 bits, "
                       "one (chunk, level) per thread" % (len(kv_host_chunks), len(kv_host_chunks) * unc_bytes >> 20),
             "wall_s": wall}, parity
@@ -384,6 +391,7 @@ def main():
         avg = sum(durs) / len(durs)
         u, b = algorithmic_bytes(l, N, c, bits, n_chunks, chunk)
         per_kernel.append({"kernel": "%s_kernel" % kind, "op": kind, "bits": bits, "avg_ms": avg, "min_ms": min(durs),
+                           "median_ms": sorted(durs)[len(durs) // 2],
                            "uncompressed_GBps": u / avg / 1e6, "algorithmic_bytes": u + b,
                            "hbm_GBps": (u + b) / avg / 1e6, "hbm_frac": (u + b) / avg / 1e6 / HBM_PEAK_GBPS,
                            "traffic": MEASURED_TRAFFIC_BYTES.get((kind, bits)) if args.workload == "llama3_8b_8k" else None})

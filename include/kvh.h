@@ -78,7 +78,8 @@ size_t kvh_blob_size(int l, int n_tokens, int c, int level);
  * elements.  Contiguous use: element (layer, token, ch) of K is k[layer*layer_stride +
  * token*token_stride + ch].  Paged use (decode only): the tensors are [l][P][block_tokens][c],
  * token_stride is the stride between slots of a block (normally c) and blocks are dense:
- * physical row = block * block_tokens + slot.  Strides are in elements. */
+ * physical row = block * block_tokens + slot.  Strides are in elements.  A destination view needs
+ * token_stride >= c (rows must not overlap); anything smaller is KVH_E_ARG. */
 typedef struct {
   void* k;
   void* v;

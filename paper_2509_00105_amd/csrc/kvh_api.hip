@@ -23,6 +23,12 @@ int check_view(const kvh_kv_view* v) {
   return KVH_OK;
 }
 
+// A destination whose rows are closer together than c elements would have rows written over each other.
+int check_dst_view(const kvh_kv_view* v, int c) {
+  if (int rc = check_view(v)) return rc;
+  return v->token_stride < c ? KVH_E_ARG : KVH_OK;
+}
+
 __global__ __launch_bounds__(kBlockThreads) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
                                                               size_t n16) {
   size_t i = (size_t)blockIdx.x * (kBlockThreads * 4) + threadIdx.x;
@@ -127,7 +133,7 @@ int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_
 int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, int level, const kvh_kv_view* dst,
                int64_t dst_token0, const int32_t* page_table_dev, int block_tokens, int32_t* status_dev, void* stream) {
   if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16) || dst_token0 < 0) return KVH_E_ARG;
-  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_dst_view(dst, c)) return rc;
   if (level_bits(level) < 0) return KVH_E_LEVEL;
   if (int rc = check_shape(l, n_tokens, c)) return rc;
   if (page_table_dev != nullptr && block_tokens < 1) return KVH_E_ARG;
@@ -153,7 +159,7 @@ int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_
   if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16) ||
       block_tokens < 1)
     return KVH_E_ARG;
-  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_dst_view(dst, c)) return rc;
   if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
   DecodeParams a{};
   a.items = items_dev;
@@ -206,7 +212,7 @@ int kvh_decode_kept(const void* blob_dev, kvh_dtype dt, int l, int N, int c, int
                     const kvh_kv_view* dst, int64_t dst_token0, int compact, const int32_t* page_table_dev,
                     int block_tokens, int32_t* status_dev, void* stream) {
   if (blob_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16) || dst_token0 < 0) return KVH_E_ARG;
-  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_dst_view(dst, c)) return rc;
   if (level_bits(level) < 0) return KVH_E_LEVEL;
   const int n = kvh_kept_tokens(N, sink, window);
   if (n < 1) return KVH_E_SHAPE;
@@ -287,7 +293,7 @@ int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_t
   if (items_dev == nullptr || n_items < 1 || n_items > kMaxItems || (dt != KVH_F16 && dt != KVH_BF16) ||
       block_tokens < 1)
     return KVH_E_ARG;
-  if (int rc = check_view(dst)) return rc;
+  if (int rc = check_dst_view(dst, c)) return rc;
   if (int rc = check_shape(l, max_tokens_per_item, c)) return rc;
   DecodeParams a{};
   a.kept_items = items_dev;

@@ -144,7 +144,7 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
                    const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream) {
   if (ld == nullptr || items == nullptr || n_items < 1 || (dt != KVH_F16 && dt != KVH_BF16) || block_tokens < 1)
     return KVH_E_ARG;
-  if (dst == nullptr || dst->k == nullptr || dst->v == nullptr || dst->layer_stride < 0 || dst->token_stride < 0)
+  if (dst == nullptr || dst->k == nullptr || dst->v == nullptr || dst->layer_stride < 0 || dst->token_stride < c)
     return KVH_E_ARG;
   if (((reinterpret_cast<uintptr_t>(dst->k) | reinterpret_cast<uintptr_t>(dst->v)) & 15u) != 0 ||
       dst->layer_stride % 8 != 0 || dst->token_stride % 8 != 0)

@@ -97,6 +97,8 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert dec(P, 0, 1, 128, 1024, 0, v, 0, P, 0, None, None) == E_ARG
     assert dec(P + 4, 0, 1, 128, 1024, 0, v, 0, None, 16, None, None) == E_ALIGN
     assert dec(P, 0, 1, 128, 1024, 0, v, 2**31 - 64, None, 16, None, None) == E_ARG
+    assert dec(P, 0, 1, 128, 1024, 0, ctypes.byref(_KVView(P, P, 1024 * 256, 512)), 0, None, 16, None, None) == E_ARG  # rows overlap
+    assert lib.kvh_decode_batch(P, 1, 256, 0, 1, 1024, ctypes.byref(_KVView(P, P, 0, 0)), 16, None, None) == E_ARG
 
     lv = (ctypes.c_int8 * 2)(0, 1)
     off = (ctypes.c_size_t * 2)(0, 1 << 20)
