@@ -228,7 +228,6 @@ template <int DT, int BITS>
 __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_enc_item& it, uint8_t* layer_base,
                                                const LayerGeom& geo, int lam, int tile, int strip, int split,
                                                int64_t jump) {
-  constexpr int kBatch = 8;  // rows in flight per wave
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = it.n_tokens;
@@ -244,18 +243,17 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
   uint8_t* codes = vmeta + geo.vmeta;  // wave-uniform
   const uint32_t lane_code_off = (uint32_t)ch0 * BITS / 8;
 
-  for (int i0 = 0; i0 < kEncRows; i0 += kBatch) {
-    if (t_first + i0 >= n) break;  // wave-uniform
-    uintx4 d[kBatch];
+  if (t_first < n) {  // wave-uniform
+    uintx4 d[kEncRows];  // all 16 rows of the wave are requested before the first one is used
 #pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      int t = t_first + i0 + i;
+    for (int i = 0; i < kEncRows; ++i) {
+      int t = t_first + i;
       t = t < n ? t : n - 1;
       d[i] = gload<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
     }
 #pragma unroll
-    for (int i = 0; i < kBatch; ++i) {
-      int t = t_first + i0 + i;
+    for (int i = 0; i < kEncRows; ++i) {
+      int t = t_first + i;
       float x[8];
       unpack8<DT>(d[i], x);
       float mn = __builtin_fminf(__builtin_fminf(x[0], x[1]), x[2]);
