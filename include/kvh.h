@@ -311,7 +311,8 @@ double kvh_policy_marginal_utility_drop(double u_m, double u_n, double size_m, d
  * tier_out[i] = tier index or -1 (evicted everywhere), choice_out[i] = chosen choice or -1; *total_utility_out
  * (nullable) = sum of the utilities of the placed entries in index order.  Host arrays throughout.
  * Errors: KVH_E_ARG (null pointer, counts < 1, non-finite or negative values, sizes not whole or not strictly
- * decreasing), KVH_E_SHAPE (an entry's choice range or min_choice out of bounds). */
+ * decreasing), KVH_E_SHAPE (an entry's choice range or min_choice out of bounds), KVH_E_SIZE (the entries'
+ * largest sizes add up to 2^53 bytes or more, where sums of doubles stop being exact). */
 int kvh_policy_plan(const kvh_policy_entry* entries, int n_entries, const double* sizes, const double* qualities,
                     int n_choices_total, const kvh_policy_tier* tiers, int n_tiers, double alpha, int32_t* tier_out,
                     int32_t* choice_out, double* total_utility_out);

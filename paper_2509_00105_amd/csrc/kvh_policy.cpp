@@ -59,6 +59,7 @@ int kvh_policy_plan(const kvh_policy_entry* entries, int n_entries, const double
     return KVH_E_ARG;
   for (int t = 0; t < n_tiers; ++t)
     if (!(tiers[t].bandwidth > 0.0) || !std::isfinite(tiers[t].bandwidth) || !(tiers[t].capacity >= 0.0)) return KVH_E_ARG;
+  double all_sizes = 0.0;  // the sum of the largest choices bounds every occupancy the search can form
   for (int i = 0; i < n_entries; ++i) {
     const kvh_policy_entry& e = entries[i];
     if (e.n_choices < 1 || e.first < 0 || (int64_t)e.first + e.n_choices > n_choices_total) return KVH_E_SHAPE;
@@ -68,6 +69,8 @@ int kvh_policy_plan(const kvh_policy_entry* entries, int n_entries, const double
       if (!integral_size(sizes[e.first + j]) || !std::isfinite(qualities[e.first + j])) return KVH_E_ARG;
       if (j > 0 && !(sizes[e.first + j] < sizes[e.first + j - 1])) return KVH_E_ARG;
     }
+    all_sizes += sizes[e.first];
+    if (!(all_sizes < 9007199254740992.0)) return KVH_E_SIZE;  // sums would stop being exact
   }
 
   std::vector<double> u((size_t)n_choices_total);

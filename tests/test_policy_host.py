@@ -135,3 +135,9 @@ def test_argument_errors(kvh):
     assert call(t=bt) == -1
     it = tr.copy(); it["capacity"] = np.inf
     assert call(t=it) == 0
+    # two entries whose largest sizes add up to 2^53: occupancy sums would no longer be exact
+    two = np.zeros(2, dtype=POLICY_ENTRY); two["freq"], two["n_choices"], two["first"] = 1.0, 1, [0, 1]
+    half = np.array([2.0 ** 52, 2.0 ** 52]); qq = np.array([1.0, 1.0])
+    to2, co2 = np.zeros(2, np.int32), np.zeros(2, np.int32)
+    assert L.kvh_policy_plan(two.ctypes.data, 2, half.ctypes.data, qq.ctypes.data, 2, tr.ctypes.data, 1, 1.0,
+                             to2.ctypes.data, co2.ctypes.data, None) == -4
