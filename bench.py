@@ -29,9 +29,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # same command (profiles/codec_kernels_llama3_8b_8k_bf16.md): (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB, the
 # factors being what the counters read for the plain copy kernel of known size.  Re-measure after kernel changes.
 MEASURED_TRAFFIC_BYTES = {
-    ("encode", 8): 1665667072, ("encode", 4): 1367820288, ("encode", 2): 1307472896,
-    ("decode", 8): 1637854208, ("decode", 4): 1369672704, ("decode", 2): 1235411968,
-    ("transcode", 8, 4): 850563072, ("transcode", 8, 2): 717382656, ("transcode", 4, 2): 444995584,
+    ("encode", 8): 1682763776, ("encode", 4): 1401620480, ("encode", 2): 1265028096,
+    ("decode", 8): 1637858304, ("decode", 4): 1369648128, ("decode", 2): 1235397632,
+    ("transcode", 8, 4): 850537472, ("transcode", 8, 2): 717331456, ("transcode", 4, 2): 445009920,
 }
 
 
