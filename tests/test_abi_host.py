@@ -173,3 +173,14 @@ def test_binding_refuses_host_tensors(lib):
     k = torch.zeros((1, 128, 128), dtype=torch.float16)
     with pytest.raises(ValueError):
         kvh.encode(k, k, 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more must end with a message, before any GPU work."""
+    import subprocess
+    import sys
+
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
