@@ -272,7 +272,9 @@ int kvh_loader_create(kvh_loader** out, void* staging_dev, size_t staging_bytes,
 size_t kvh_loader_slot_bytes(const kvh_loader* loader);
 /* Enqueue, group by group in item order: wait until the next slot is free, copy the group's blobs host ->
  * slot on the loader's copy stream, then decode them on `stream` into `dst` (contiguous or paged, as
- * kvh_decode_kept_batch: ordinary and token-dropped blobs may be mixed).  Returns once everything is enqueued; results
+ * kvh_decode_kept_batch: ordinary and token-dropped blobs may be mixed).  The copies start after the work already
+ * enqueued on `stream` (so blobs that an earlier call on it writes into host memory are complete when they are
+ * read).  Returns once everything is enqueued; results
  * are valid after `stream` has been synchronised; host blobs and the staging buffer must stay alive until
  * then.  status_dev, if not NULL, has one zeroed int32 per item (KVH_DEV_HEADER_MISMATCH as for
  * kvh_decode_batch).  All items are validated before anything is enqueued. */

@@ -8,7 +8,7 @@
 // head of the slot, then decoded by ONE batched decode launch.  Per-blob runtime copies were
 // measured to leave 30-60 us of idle bus between two copies on this platform; with groups the
 // fixed costs are paid once per slot.  Two streams (copy, caller's compute) and two events per slot
-// order the ring.
+// order the ring; one more event orders a run's copies after what the caller's stream already holds.
 #include <new>
 
 #include "kvh_common.hpp"
@@ -73,6 +73,7 @@ struct kvh_loader {
   hipStream_t copy_stream;
   hipEvent_t* copied;  // [slot] the slot's group has arrived
   hipEvent_t* freed;   // [slot] the decode that read the slot has finished
+  hipEvent_t entered;  // the caller's stream at the start of a run
   bool* in_use;        // [slot] `freed` has been recorded at least once
 };
 
@@ -82,6 +83,7 @@ namespace {
 void destroy(kvh_loader* ld) {
   if (ld == nullptr) return;
   if (ld->copy_stream != nullptr) (void)hipStreamDestroy(ld->copy_stream);
+  if (ld->entered != nullptr) (void)hipEventDestroy(ld->entered);
   for (int s = 0; s < ld->n_slots; ++s) {
     if (ld->copied != nullptr && ld->copied[s] != nullptr) (void)hipEventDestroy(ld->copied[s]);
     if (ld->freed != nullptr && ld->freed[s] != nullptr) (void)hipEventDestroy(ld->freed[s]);
@@ -118,6 +120,7 @@ int kvh_loader_create(kvh_loader** out, void* staging_dev, size_t staging_bytes,
   bool ok = ld->copied != nullptr && ld->freed != nullptr && ld->in_use != nullptr;
   // default priority; non-blocking so that the legacy default stream does not serialise the copies
   ok = ok && hipStreamCreateWithFlags(&ld->copy_stream, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ld->entered, hipEventDisableTiming) == hipSuccess;
   for (int s = 0; ok && s < n_slots; ++s) {
     ok = hipEventCreateWithFlags(&ld->copied[s], hipEventDisableTiming) == hipSuccess &&
          hipEventCreateWithFlags(&ld->freed[s], hipEventDisableTiming) == hipSuccess;
@@ -174,6 +177,10 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
     if (it.dst_token0 + span > INT32_MAX) return KVH_E_ARG;
   }
   hipStream_t compute = static_cast<hipStream_t>(stream);
+  // Stream order: the copies read host blobs that work already enqueued on the caller's stream may
+  // still be writing (an encode straight into pinned memory), so they start after that work.
+  if (hipEventRecord(ld->entered, compute) != hipSuccess || hipStreamWaitEvent(ld->copy_stream, ld->entered, 0) != hipSuccess)
+    return KVH_E_HIP;
   DecodeParams a{};
   a.k = static_cast<uint16_t*>(dst->k);
   a.v = static_cast<uint16_t*>(dst->v);

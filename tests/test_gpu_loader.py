@@ -181,3 +181,38 @@ def test_loader_takes_token_dropped_blobs(kvh):
     with pytest.raises(kvh.KVHError):  # n_tokens that is not what the drop words keep
         ld.run(blobs[:1], [n_kept - 1], [2], [0], gk, gv, drops=[(N, sink, window, False)])
     ld.close()
+
+
+def test_store_then_load_on_one_stream_without_a_sync_between(kvh):
+    """Stream order across the two directions: blobs encoded straight into pinned host memory on a stream are
+    loaded back by a run enqueued on the same stream right after, with no host synchronisation in between."""
+    dt, l, c, chunk = BF16, 4, 1024, 256
+    n_chunks = 12
+    N = n_chunks * chunk
+    levels = [i % 3 for i in range(n_chunks)]
+    k, v = gen.make_kv(l, N, c, dt, seed=97)
+    kd = torch.from_numpy(k.view(np.int16)).cuda().view(torch.bfloat16)
+    vd = torch.from_numpy(v.view(np.int16)).cuda().view(torch.bfloat16)
+    sizes = [kvh.blob_size(l, chunk, c, lv) for lv in levels]
+    host = [torch.full((s,), 0xEE, dtype=torch.uint8).pin_memory() for s in sizes]
+    items = kvh.make_enc_items([h.data_ptr() for h in host], [i * chunk for i in range(n_chunks)], [chunk] * n_chunks,
+                               levels, "cuda")
+    staging = torch.empty(2 * (2 * max(sizes) + 1536), dtype=torch.uint8, device="cuda")
+    ld = kvh.Loader(staging, 2)
+    ok = torch.zeros((l, N, c), dtype=torch.bfloat16, device="cuda"); ov = torch.zeros_like(ok)
+    status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        kvh.encode_batch(items, n_chunks, chunk, kd, vd, stream=s)
+        ld.run(host, [chunk] * n_chunks, levels, [i * chunk for i in range(n_chunks)], ok, ov, status=status, stream=s)
+    s.synchronize()
+    assert status.cpu().tolist() == [0] * n_chunks
+    wk, wv = np.zeros_like(k), np.zeros_like(v)
+    for i, lv in enumerate(levels):
+        sl = slice(i * chunk, (i + 1) * chunk)
+        b = oracle.encode(np.ascontiguousarray(k[:, sl]), np.ascontiguousarray(v[:, sl]), dt, lv)
+        assert np.array_equal(host[i].numpy(), b), ("stored blob", i)
+        wk[:, sl], wv[:, sl] = oracle.decode(b, dt, l, chunk, c, lv)
+    assert np.array_equal(to_host(ok), wk) and np.array_equal(to_host(ov), wv)
+    ld.close()
