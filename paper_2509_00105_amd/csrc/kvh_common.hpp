@@ -7,6 +7,33 @@
 
 #include "../../include/kvh.h"
 
+#include <cstddef>
+
+// The kernels read job descriptors as raw 16-byte words and the binding builds them as packed records:
+// the layouts below are part of the ABI.
+static_assert(sizeof(kvh_enc_item) == 24 && offsetof(kvh_enc_item, src_token0) == 8 &&
+                  offsetof(kvh_enc_item, n_tokens) == 16 && offsetof(kvh_enc_item, level) == 20,
+              "kvh_enc_item layout");
+static_assert(sizeof(kvh_item) == 32 && offsetof(kvh_item, n_tokens) == 8 && offsetof(kvh_item, level) == 12 &&
+                  offsetof(kvh_item, dst_token0) == 16 && offsetof(kvh_item, page_table) == 24,
+              "kvh_item layout");
+static_assert(sizeof(kvh_kept_enc_item) == 32 && offsetof(kvh_kept_enc_item, src_token0) == 8 &&
+                  offsetof(kvh_kept_enc_item, orig_tokens) == 16 && offsetof(kvh_kept_enc_item, sink) == 20 &&
+                  offsetof(kvh_kept_enc_item, window) == 24 && offsetof(kvh_kept_enc_item, level) == 28,
+              "kvh_kept_enc_item layout");
+static_assert(sizeof(kvh_kept_item) == 48 && offsetof(kvh_kept_item, n_tokens) == 8 && offsetof(kvh_kept_item, level) == 12 &&
+                  offsetof(kvh_kept_item, dst_token0) == 16 && offsetof(kvh_kept_item, page_table) == 24 &&
+                  offsetof(kvh_kept_item, orig_tokens) == 32 && offsetof(kvh_kept_item, sink) == 36 &&
+                  offsetof(kvh_kept_item, window) == 40 && offsetof(kvh_kept_item, compact) == 44,
+              "kvh_kept_item layout");
+static_assert(sizeof(kvh_tc_item) == 32 && offsetof(kvh_tc_item, dst) == 8 && offsetof(kvh_tc_item, n_tokens) == 16 &&
+                  offsetof(kvh_tc_item, level_in) == 20 && offsetof(kvh_tc_item, level_out) == 24,
+              "kvh_tc_item layout");
+static_assert(sizeof(kvh_load_item) == 48 && offsetof(kvh_load_item, n_tokens) == 8 && offsetof(kvh_load_item, level) == 12 &&
+                  offsetof(kvh_load_item, dst_token0) == 16 && offsetof(kvh_load_item, page_table) == 24 &&
+                  offsetof(kvh_load_item, orig_tokens) == 32 && offsetof(kvh_load_item, compact) == 44,
+              "kvh_load_item layout");
+
 namespace kvh {
 
 constexpr int kGroup = 128;        // tokens per K group and channels per V group

@@ -7,11 +7,17 @@
 // (size, utility) and so reaches the optimum of the linear relaxation up to one fractional step.
 // Ties: smaller drop, then lower entry index, then larger remaining size.
 #include <cmath>
+#include <cstddef>
 #include <cstdint>
 #include <queue>
 #include <vector>
 
 #include "../../include/kvh.h"
+
+static_assert(sizeof(kvh_policy_entry) == 24 && offsetof(kvh_policy_entry, first) == 8 &&
+                  offsetof(kvh_policy_entry, n_choices) == 12 && offsetof(kvh_policy_entry, min_choice) == 16,
+              "kvh_policy_entry layout");
+static_assert(sizeof(kvh_policy_tier) == 16 && offsetof(kvh_policy_tier, capacity) == 8, "kvh_policy_tier layout");
 
 namespace {
 

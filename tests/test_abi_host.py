@@ -184,3 +184,40 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_records_have_the_layout_of_the_c_structs(tmp_path):
+    """The binding marshals descriptors as numpy records; a C program compiled against include/kvh.h prints
+    sizeof/offsetof of every struct field and the two must agree name by name."""
+    import subprocess
+
+    from paper_2509_00105_amd import binding as b
+
+    records = {"kvh_enc_item": b.ENC_ITEM, "kvh_item": b.DEC_ITEM, "kvh_tc_item": b.TC_ITEM,
+               "kvh_load_item": b.LOAD_ITEM, "kvh_kept_enc_item": b.KEPT_ENC_ITEM, "kvh_kept_item": b.KEPT_ITEM,
+               "kvh_policy_entry": b.POLICY_ENTRY, "kvh_policy_tier": b.POLICY_TIER}
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "kvh.h"', 'int main(void) {']
+    for name, dt in records.items():
+        lines.append('  printf("%s size %%zu\\n", sizeof(%s));' % (name, name))
+        for field in dt.names:
+            lines.append('  printf("%s %s %%zu\\n", offsetof(%s, %s));' % (name, field, name, field))
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen = 0
+    for line in out:
+        if not line:
+            continue
+        name, field, value = line.split()
+        dt = records[name]
+        if field == "size":
+            assert dt.itemsize == int(value), (name, dt.itemsize, value)
+        else:
+            assert dt.fields[field][1] == int(value), (name, field, dt.fields[field][1], value)
+        seen += 1
+    assert seen == sum(len(dt.names) + 1 for dt in records.values())
+    view = b._KVView
+    assert ctypes.sizeof(view) == 32 and [f[0] for f in view._fields_] == ["k", "v", "layer_stride", "token_stride"]
