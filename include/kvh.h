@@ -111,8 +111,10 @@ typedef struct {
 
 /* Compress many chunks of one source view in ONE launch.  The host cannot see the items, so
  * the caller guarantees their validity (levels in range, blobs large enough and disjoint,
- * source rows inside the view); items with n_tokens < 1 or a bad level are skipped by the
- * kernel.  n_items <= 65535. */
+ * source rows inside the view).  What the kernel can see it enforces: an item with n_tokens < 1,
+ * a bad level, or n_tokens > max_tokens_per_item (more rows than the launch covers) is skipped as
+ * a whole — nothing is written to its blob, not even the header, so a later decode of that buffer
+ * reports KVH_DEV_HEADER_MISMATCH rather than returning half an entry.  n_items <= 65535. */
 int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
                      const kvh_kv_view* src, void* stream);
 
@@ -140,7 +142,10 @@ typedef struct {
 /* Decompress many blobs (mixed levels, mixed lengths) into one destination view in ONE launch.
  * status_dev, if not NULL, is an int32 array of n_items entries (zeroed by the caller); entry i
  * is set to KVH_DEV_HEADER_MISMATCH when item i's header disagrees, and that item writes
- * nothing.  Items whose n_tokens < 1 or level is out of range are skipped the same way.
+ * nothing.  The same happens to an item whose level is out of range, whose n_tokens exceeds
+ * max_tokens_per_item (more rows than the launch covers), or whose rows would leave the 31-bit row
+ * range (dst_token0 < 0 or dst_token0 + n_tokens > 2^31 - 1): refused as a whole, never decoded in
+ * part.  Items with n_tokens < 1 are skipped silently.
  * Destinations of different items must not overlap.  n_items <= 65535. */
 int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
                      const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
@@ -183,7 +188,8 @@ typedef struct {
 
 /* kvh_encode_kept for many entries of one source view in ONE launch.  max_kept_tokens_per_item bounds
  * kvh_kept_tokens(orig_tokens, sink, window) over the items.  The caller guarantees the items' validity
- * (as for kvh_encode_batch); items with a bad level or nothing kept are skipped.  n_items <= 65535. */
+ * (as for kvh_encode_batch); items with a bad level, nothing kept, or more kept tokens than
+ * max_kept_tokens_per_item are skipped as a whole (no header is written).  n_items <= 65535. */
 int kvh_encode_kept_batch(const kvh_kept_enc_item* items_dev, int n_items, int max_kept_tokens_per_item, kvh_dtype dt,
                           int l, int c, const kvh_kv_view* src, void* stream);
 
@@ -201,8 +207,9 @@ typedef struct {
 } kvh_kept_item;
 
 /* kvh_decode_batch over items that may be token-dropped (mixed with ordinary ones).  An item whose header
- * disagrees, or whose n_tokens is not what (orig_tokens, sink, window) keep, gets KVH_DEV_HEADER_MISMATCH
- * and writes nothing. */
+ * disagrees, whose n_tokens is not what (orig_tokens, sink, window) keep, or which kvh_decode_batch would
+ * refuse (n_tokens > max_tokens_per_item; rows outside the 31-bit range, counting orig_tokens rows for an
+ * entry decoded back to its original positions) gets KVH_DEV_HEADER_MISMATCH and writes nothing. */
 int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l,
                           int c, const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream);
 
@@ -235,8 +242,9 @@ typedef struct {
 } kvh_tc_item;
 
 /* Transcode many blobs (mixed lengths and level pairs) in ONE launch.  status_dev as for
- * kvh_decode_batch; items with n_tokens < 1 are skipped, items with a level out of range get
- * KVH_DEV_HEADER_MISMATCH.  Buffers of different items must not overlap.  n_items <= 65535. */
+ * kvh_decode_batch; items with n_tokens < 1 are skipped, items with a level out of range or with
+ * n_tokens > max_tokens_per_item get KVH_DEV_HEADER_MISMATCH and write nothing (no destination
+ * header either).  Buffers of different items must not overlap.  n_items <= 65535. */
 int kvh_transcode_batch(const kvh_tc_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
                         int32_t* status_dev, void* stream);
 

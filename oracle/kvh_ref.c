@@ -369,9 +369,9 @@ void kvh_ref_f32_to_t16_array(const float* in, uint16_t* out, size_t count, int 
 }
 
 /* ------------------------------------------------------------------------------------------
- * Token dropping (the paper's second compression method: Introduction, "some texts are only
- * important at the beginning and the end"; Preliminary Results, the fixed-rate token-dropping
- * baseline).  The paper gives no definition; the reading taken: keep the first `sink` and the
+ * Token dropping (the paper's second compression method: the Introduction motivates it with
+ * contexts whose middle matters little compared with their start and their end; Preliminary
+ * Results use it as the fixed-rate token-dropping baseline).  The paper gives no definition; the reading taken: keep the first `sink` and the
  * last `window` tokens of an entry of N tokens, drop the middle, and store the kept tokens at a
  * quantised level.  Written as the plain composition gather -> encode and decode -> scatter.
  * ---------------------------------------------------------------------------------------- */

@@ -358,7 +358,10 @@ def transcode(blob: torch.Tensor, dtype, l: int, n_tokens: int, c: int, level_in
         if size == 0:
             _check(lib().kvh_transcode(blob.data_ptr(), dt, l, n_tokens, c, level_in, level_out, None, 0, None, None),
                    "kvh_transcode")
-        out = torch.empty(size, dtype=torch.uint8, device=blob.device)
+        # A source in pinned host memory has device "cpu": the default output still has to be memory the
+        # kernel can write, so it goes to the current GPU (pass `out=` to write into the host tier instead).
+        out = torch.empty(size, dtype=torch.uint8, device=blob.device if blob.is_cuda else torch.device("cuda"))
+        _require_visible(out)
     _check(lib().kvh_transcode(blob.data_ptr(), dt, l, n_tokens, c, level_in, level_out, out.data_ptr(), out.numel(),
                                status.data_ptr() if status is not None else None, _stream_ptr(stream)), "kvh_transcode")
     return out

@@ -137,6 +137,7 @@ struct DecodeParams {
   int64_t layer_stride, token_stride;  // elements
   int32_t* status;                     // nullable; indexed by item
   int l, c, block_tokens;
+  int max_tokens;  // rows the grid covers per item: an item with more tokens is refused on the device
   // Token-dropped entries (single-item calls only): token t >= split lands `jump` rows further on,
   // and the header must carry these three words (all zero for an ordinary blob).
   int32_t split;
@@ -152,6 +153,7 @@ struct EncodeParams {
   const uint16_t* v;
   int64_t layer_stride, token_stride;  // elements
   int l, c;
+  int max_tokens;  // rows the grid covers per item: an item with more tokens is skipped on the device
   // Token-dropped entries (single-item calls only): token t >= split is read `jump` rows further on,
   // and the header records these three words (all zero for an ordinary blob).
   int32_t split;
@@ -174,6 +176,7 @@ struct TranscodeParams {
   kvh_tc_item one;
   int32_t* status;           // nullable; indexed by item
   int l, c;
+  int max_tokens;            // rows the grid covers per item: an item with more tokens is refused on the device
 };
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);

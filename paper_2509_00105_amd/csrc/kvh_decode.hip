@@ -351,6 +351,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   it.level = uniform(it.level);
   it.dst_token0 = uniform(it.dst_token0);
   it.page_table = uniform(it.page_table);
+  // An item with more tokens than the grid covers, or whose rows leave the 31-bit row range, is refused as a
+  // whole: partial output with a clean status word would be worse than none.
+  {
+    const int64_t reach = drop.split != kNoSplit ? (int64_t)drop.orig_tokens : (int64_t)it.n_tokens;
+    if (it.n_tokens > a.max_tokens || it.dst_token0 < 0 || it.dst_token0 + reach > 0x7fffffffLL) consistent = false;
+  }
   __shared__ float kshare[3 * kDecSpanCh];  // K parameters of the block's span: minima, scales, top codes
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
@@ -374,10 +380,12 @@ int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hi
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
   const unsigned gx = (unsigned)(((max_tokens + kDecRows * kDecWaves - 1) / (kDecRows * kDecWaves)) * nspans);
   dim3 grid(gx, (unsigned)(2 * a.l), (unsigned)n_items);
+  DecodeParams b = a;
+  b.max_tokens = max_tokens;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, a);
+    hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, b);
   else
-    hipLaunchKernelGGL(decode_kernel<KVH_BF16>, grid, dim3(kDecThreads), 0, stream, a);
+    hipLaunchKernelGGL(decode_kernel<KVH_BF16>, grid, dim3(kDecThreads), 0, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

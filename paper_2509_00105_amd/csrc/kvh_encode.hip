@@ -332,7 +332,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   const int tile = blockIdx.x / nstrips;
   const int strip = blockIdx.x - tile * nstrips;
   const int bits = level_bits(it.level);
-  if (bits < 0 || it.n_tokens < 1 || tile * kEncTile >= it.n_tokens) return;  // block-uniform
+  // block-uniform; an item with more tokens than the grid covers is skipped as a whole (no header either), so
+  // that a later decode of its blob reports a mismatch instead of reading sections that were never written
+  if (bits < 0 || it.n_tokens < 1 || it.n_tokens > a.max_tokens || tile * kEncTile >= it.n_tokens) return;
   const LayerGeom geo = layer_geom(it.n_tokens, a.c, bits);
   uint8_t* blob = static_cast<uint8_t*>(it.blob);
   const int lam = blockIdx.y >> 1;
@@ -377,10 +379,12 @@ int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hi
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
   const int tiles = (max_tokens + kEncTile - 1) / kEncTile;
   dim3 grid((unsigned)(tiles * nstrips), (unsigned)(2 * a.l), (unsigned)n_items);
+  EncodeParams b = a;
+  b.max_tokens = max_tokens;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(encode_kernel<KVH_F16>, grid, dim3(kEncThreads), 0, stream, a);
+    hipLaunchKernelGGL(encode_kernel<KVH_F16>, grid, dim3(kEncThreads), 0, stream, b);
   else
-    hipLaunchKernelGGL(encode_kernel<KVH_BF16>, grid, dim3(kEncThreads), 0, stream, a);
+    hipLaunchKernelGGL(encode_kernel<KVH_BF16>, grid, dim3(kEncThreads), 0, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

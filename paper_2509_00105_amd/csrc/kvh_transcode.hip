@@ -597,7 +597,7 @@ __global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(Transc
   const int lam = blockIdx.y >> 1;
   const bool is_v = blockIdx.y & 1;
   const int bi = level_bits(it.level_in), bo = level_bits(it.level_out);
-  if (bi < 0 || bo < 0) {
+  if (bi < 0 || bo < 0 || it.n_tokens > a.max_tokens) {  // also: more tokens than the grid covers
     if (a.status != nullptr && threadIdx.x == 0) a.status[blockIdx.z] = KVH_DEV_HEADER_MISMATCH;
     return;
   }
@@ -616,10 +616,12 @@ int launch_transcode(const TranscodeParams& a, int dt, int n_items, int max_toke
   const int nspans = (a.c + kTcSpanCh - 1) / kTcSpanCh;
   const int groups = (max_tokens + kGroup - 1) / kGroup;
   dim3 grid((unsigned)(groups * nspans), (unsigned)(2 * a.l), (unsigned)n_items);
+  TranscodeParams b = a;
+  b.max_tokens = max_tokens;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(transcode_kernel<KVH_F16>, grid, dim3(kTcThreads), 0, stream, a);
+    hipLaunchKernelGGL(transcode_kernel<KVH_F16>, grid, dim3(kTcThreads), 0, stream, b);
   else
-    hipLaunchKernelGGL(transcode_kernel<KVH_BF16>, grid, dim3(kTcThreads), 0, stream, a);
+    hipLaunchKernelGGL(transcode_kernel<KVH_BF16>, grid, dim3(kTcThreads), 0, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

@@ -175,6 +175,58 @@ def test_binding_refuses_host_tensors(lib):
         kvh.encode(k, k, 0)
 
 
+def test_transcode_default_output_is_device_memory_for_a_pinned_host_source(monkeypatch):
+    """A source blob in pinned host memory reports device "cpu"; the output the binding allocates by default
+    must still be memory the kernel can write (the launch itself is mocked: nothing runs)."""
+    import torch
+
+    from paper_2509_00105_amd import binding as b
+
+    class FakeTensor:
+        def __init__(self, is_cuda, pinned, n=4096):
+            self.is_cuda, self._pinned, self._n, self.device = is_cuda, pinned, n, torch.device("cuda" if is_cuda else "cpu")
+
+        def is_pinned(self):
+            return self._pinned
+
+        def data_ptr(self):
+            return 0x10000
+
+        def numel(self):
+            return self._n
+
+    class FakeLib:
+        def __init__(self):
+            self.calls = []
+
+        def kvh_blob_size(self, l, n, c, level):
+            return 4096
+
+        def kvh_transcode(self, *args):
+            self.calls.append(args)
+            return 0
+
+    fake = FakeLib()
+    asked = []
+
+    def fake_empty(size, dtype=None, device=None):
+        asked.append(torch.device(device))
+        return FakeTensor(torch.device(device).type == "cuda", False, size)
+
+    monkeypatch.setattr(b, "lib", lambda: fake)
+    monkeypatch.setattr(b, "_stream_ptr", lambda s: 0)
+    monkeypatch.setattr(b.torch, "empty", fake_empty)
+    out = b.transcode(FakeTensor(False, True), b.BF16, 1, 128, 128, 0, 1)     # pinned host source
+    assert asked[-1].type == "cuda" and out.is_cuda and len(fake.calls) == 1
+    out = b.transcode(FakeTensor(True, False), b.BF16, 1, 128, 128, 0, 1)     # device source
+    assert asked[-1].type == "cuda" and len(fake.calls) == 2
+    with pytest.raises(ValueError):                                           # pageable host source
+        b.transcode(FakeTensor(False, False), b.BF16, 1, 128, 128, 0, 1)
+    with pytest.raises(ValueError):                                           # pageable host destination
+        b.transcode(FakeTensor(True, False), b.BF16, 1, 128, 128, 0, 1, out=FakeTensor(False, False))
+    assert len(fake.calls) == 2
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU; asking for more must end with a message, before any GPU work."""
     import subprocess
