@@ -9,7 +9,12 @@ outputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line: the whole-step throughput in GB/s of uncompressed KV, per-kernel
 figures, the HBM roofline of the dominant kernel (algorithmic bytes / HIP-event duration) and
-the CPU oracle timed on the host cores over a bounded sample of the same workload.
+the CPU oracle timed on the host cores over a bounded sample of the same workload.  After the
+timed region the same run also measures, as extra keys of that line: what the memory system
+gives plain read / fill / copy / mixed streams (`memory_probes`), the streamed chunk-by-chunk
+forms of the headline workload, and decode on the other workload shapes (`other_workloads`:
+Llama-3-70B-shaped 32K tokens, a 128K-token context streamed and batched, and a mixed batch of
+64 requests decoded into a paged cache).
 """
 from __future__ import annotations
 
@@ -25,14 +30,38 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
-# HBM bytes per launch on the llama3_8b_8k workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# same command (profiles/codec_kernels_llama3_8b_8k_bf16.md): (2.0 * FETCH_SIZE + 1.0 * WRITE_SIZE) KiB, the
-# factors being what the counters read for the plain copy kernel of known size.  Re-measure after kernel changes.
-MEASURED_TRAFFIC_BYTES = {
-    ("encode", 8): 1682763776, ("encode", 4): 1401620480, ("encode", 2): 1265028096,
-    ("decode", 8): 1637858304, ("decode", 4): 1369648128, ("decode", 2): 1235397632,
-    ("transcode", 8, 4): 850537472, ("transcode", 8, 2): 717331456, ("transcode", 4, 2): 445009920,
-}
+PROFILE_SUMMARY = os.path.join(ROOT, "profiles", "codec_kernels_llama3_8b_8k_bf16.md")
+
+
+def profiled_traffic(path=PROFILE_SUMMARY):
+    """HBM bytes per launch on the llama3_8b_8k workload as the committed rocprofv3 summary records them (the
+    `traffic B` column of its per-kernel table: FETCH_SIZE / WRITE_SIZE counter runs of this same command, scaled by
+    what the counters read for the plain copy kernel).  Counters cannot be read inside this run, so `traffic` in the
+    output is this profiled figure, read from the file that documents it; {} if the file is not there."""
+    out = {}
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return out
+    head = next((ln for ln in lines if ln.startswith("| kernel |")), None)
+    if head is None:
+        return out
+    col = [h.strip() for h in head.strip("|").split("|")].index("traffic B")
+    names = {"enc": "encode", "dec": "decode"}
+    for ln in lines:
+        cells = [x.strip() for x in ln.strip("|").split("|")]
+        if not ln.startswith("|") or len(cells) <= col or not cells[col].isdigit():
+            continue
+        k = cells[0]
+        if k[:3] in names and k[3:].isdigit():
+            out[(names[k[:3]], int(k[3:]))] = int(cells[col])
+        elif k.startswith("transcode ") and "->" in k:
+            a, b = k.split()[1].split("->")
+            out[("transcode", int(a), int(b))] = int(cells[col])
+    return out
+
+
+MEASURED_TRAFFIC_BYTES = profiled_traffic()
 
 
 def parse():
@@ -42,7 +71,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_8k", choices=["llama3_8b_8k", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--cpu-sample-chunks", type=int, default=16)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=32)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip everything after the timed region except what the headline line needs")
     return ap.parse_args()
 
 
@@ -57,43 +88,209 @@ def algorithmic_bytes(l, n_tokens_total, c, bits, n_chunks, chunk):
 
 
 def cpu_baseline(kv_host_chunks, dt, l, chunk, c, gpu_blobs):
-    """Time the oracle (as it stands) on the host cores over the sampled chunks; also check the
-    GPU's blobs for those chunks against it."""
+    """Time the oracle (as it stands) on the host cores over the sampled chunks, encode and decode separately;
+    also check the GPU's blobs for those chunks against it.  Then the tiny workload in full, the same way."""
     import concurrent.futures as cf
 
     import numpy as np
 
+    import kv_inputs as gen
     import oracle
 
     cores = min(os.cpu_count() or 1, 16, max(1, len(kv_host_chunks) * 3))
     oracle.lib()
 
-    def job(args):
-        ci, level = args
-        k, v = kv_host_chunks[ci]
-        blob = oracle.encode(k, v, dt, level)
-        oracle.decode(blob, dt, l, chunk, c, level)
-        return ci, level, blob
+    def timed(pairs, dt_, l_, n_, c_, threads):
+        """pairs: list of (k, v) host chunks -> (encode GB/s, decode GB/s, blobs) over all three levels."""
+        tasks = [(ci, level) for level in range(3) for ci in range(len(pairs))]
+        unc = 2 * l_ * n_ * c_ * 2
+        with cf.ThreadPoolExecutor(max_workers=threads) as ex:
+            t0 = time.perf_counter()
+            blobs = list(ex.map(lambda a: oracle.encode(pairs[a[0]][0], pairs[a[0]][1], dt_, a[1]), tasks))
+            t1 = time.perf_counter()
+            list(ex.map(lambda a: oracle.decode(a[1], dt_, l_, n_, c_, a[0][1]), zip(tasks, blobs)))
+            t2 = time.perf_counter()
+        return unc * len(tasks) / (t1 - t0) / 1e9, unc * len(tasks) / (t2 - t1) / 1e9, dict(zip(tasks, blobs)), t2 - t0
 
     unc_bytes = 2 * l * chunk * c * 2
-    # one thread first: the first sampled chunk at each level, encode + decode
-    t0 = time.perf_counter()
-    for level in range(3):
-        job((0, level))
-    single_gbps = 3 * 2 * unc_bytes / (time.perf_counter() - t0) / 1e9
-
-    tasks = [(ci, level) for level in range(3) for ci in range(len(kv_host_chunks))]
-    t0 = time.perf_counter()
-    with cf.ThreadPoolExecutor(max_workers=cores) as ex:
-        results = list(ex.map(job, tasks))
-    wall = time.perf_counter() - t0
-    total = unc_bytes * 2 * len(tasks)  # encode + decode of every (chunk, level)
-    parity = all(np.array_equal(blob, gpu_blobs[(ci, level)]) for ci, level, blob in results)
+    one_enc, one_dec, _, _ = timed(kv_host_chunks[:1], dt, l, chunk, c, 1)       # one thread, first sampled chunk
+    enc, dec, blobs, wall = timed(kv_host_chunks, dt, l, chunk, c, cores)
+    parity = all(np.array_equal(blob, gpu_blobs[key]) for key, blob in blobs.items())
+    del blobs
+    tiny = gen.CONFIGS["tiny"]
+    tk, tv = gen.make_kv(tiny.l, tiny.n, tiny.c, tiny.dtype, tiny.seed)
+    tchunks = [(np.ascontiguousarray(tk[:, t0:t0 + tiny.chunk]), np.ascontiguousarray(tv[:, t0:t0 + tiny.chunk]))
+               for t0 in range(0, tiny.n, tiny.chunk)]
+    t_enc1, t_dec1, _, _ = timed(tchunks, tiny.dtype, tiny.l, tiny.chunk, tiny.c, 1)
+    t_enc, t_dec, _, t_wall = timed(tchunks, tiny.dtype, tiny.l, tiny.chunk, tiny.c, min(cores, 3 * len(tchunks)))
+    total = 2 * unc_bytes * 3 * len(kv_host_chunks)  # encode + decode of every (chunk, level)
     return {"value": total / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "single_thread_GBps": single_gbps,
-            "sample": "%d of the workload's 256-token chunks (%d MiB uncompressed), encode+decode at 8/4/2 bits, "
-                      "one (chunk, level) per thread" % (len(kv_host_chunks), len(kv_host_chunks) * unc_bytes >> 20),
-            "wall_s": wall}, parity
+            "encode_GBps": enc, "decode_GBps": dec,
+            "single_thread_encode_GBps": one_enc, "single_thread_decode_GBps": one_dec,
+            "sample": "%d of the workload's %d-token chunks (%d MiB uncompressed), each encoded and then decoded at "
+                      "8/4/2 bits, one (chunk, level) per thread; `value` counts the bytes once for encode and once "
+                      "for decode, like the GPU figure" % (len(kv_host_chunks), chunk, len(kv_host_chunks) * unc_bytes >> 20),
+            "wall_s": wall,
+            "tiny_workload_in_full": {"workload": tiny.name, "encode_GBps": t_enc, "decode_GBps": t_dec,
+                                      "single_thread_encode_GBps": t_enc1, "single_thread_decode_GBps": t_dec1,
+                                      "threads": min(cores, 3 * len(tchunks)), "wall_s": t_wall}}, parity
+
+
+def event_pair(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def time_reps(torch, stream, fn, reps, warm=1):
+    """Average / median / min milliseconds of fn() (which enqueues on `stream`), each repetition bracketed by events."""
+    for _ in range(warm):
+        fn()
+    evs = [event_pair(torch) for _ in range(reps)]
+    for a, b in evs:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return {"avg_ms": sum(ms) / len(ms), "median_ms": ms[len(ms) // 2], "min_ms": ms[0]}
+
+
+def rate_fields(t, unc_bytes, blob_bytes):
+    """Throughput fields of one timed form: uncompressed GB/s and algorithmic fraction of the HBM peak."""
+    t = dict(t)
+    t["uncompressed_GBps"] = unc_bytes / t["avg_ms"] / 1e6
+    t["algorithmic_bytes"] = unc_bytes + blob_bytes
+    t["hbm_frac"] = (unc_bytes + blob_bytes) / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS
+    return t
+
+
+def memory_probes(torch, kvh, stream, src, dst):
+    """Plain streams over 1 GiB buffers: what this device gives a pure read, a pure fill, a copy, and streams with
+    the codec's read : write mixes and no arithmetic.  GB/s counts bytes read plus bytes written."""
+    out = {}
+    gib = 1 << 30
+    forms = [("read", 1, 0), ("fill", 0, 1), ("copy", 1, 1), ("read1_write2_like_decode8", 1, 2),
+             ("read1_write4_like_decode4", 1, 4), ("read1_write8_like_decode2", 1, 8),
+             ("read2_write1_like_encode8", 2, 1), ("read4_write1_like_encode4", 4, 1), ("read8_write1_like_encode2", 8, 1)]
+    with torch.cuda.stream(stream):
+        for name, r, w in forms:
+            units = gib // (16 * max(r, w))
+            t = time_reps(torch, stream, lambda: kvh.stream_probe(dst, src, units, r, w, stream=stream), 5)
+            moved = units * 16 * (r + w)
+            out[name] = {"avg_ms": t["avg_ms"], "bytes": moved, "GBps": moved / t["avg_ms"] / 1e6,
+                         "hbm_frac": moved / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS}
+    return out
+
+
+def other_workloads(torch, np, gen, kvh, stream, reps=5):
+    """Decode (and encode, for context) on the other workload shapes, each tensor generated once and freed before the
+    next: Llama-3-70B-shaped 32K tokens at every level; a 128K-token context at 8 and 2 bits, streamed (one launch
+    per chunk, one stream, one synchronisation) and batched; 64 requests of mixed lengths with a level per chunk,
+    decoded by ONE batched launch into a paged cache through permuted page tables."""
+    dev = torch.device("cuda:0")
+    res = {}
+
+    def plan(l, N, c, chunk, level_of):
+        spans = [(t0, min(chunk, N - t0)) for t0 in range(0, N, chunk)]
+        levels = [level_of(i) for i in range(len(spans))]
+        sizes = [kvh.blob_size(l, n, c, lv) for (_, n), lv in zip(spans, levels)]
+        offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+        return spans, levels, sizes, offs
+
+    with torch.cuda.stream(stream):
+        # ---- Llama-3-70B-shaped, 32K tokens, 512-token chunks ----
+        cfg = gen.CONFIGS["llama3_70b_32k"]
+        l, N, c, chunk = cfg.l, cfg.n, cfg.c, cfg.chunk
+        kv = gen.make_kv_device(l, N, c, cfg.dtype, cfg.seed, device=dev, drift=cfg.drift)
+        out = torch.empty_like(kv)
+        unc = kv.numel() * 2
+        rows = []
+        for level in range(3):
+            spans, levels, sizes, offs = plan(l, N, c, chunk, lambda i: level)
+            blobs = torch.empty(int(sum(sizes)), dtype=torch.uint8, device=dev)
+            ptrs = [blobs.data_ptr() + int(o) for o in offs]
+            ei = kvh.make_enc_items(ptrs, [t0 for t0, _ in spans], [n for _, n in spans], levels, dev)
+            di = kvh.make_dec_items(ptrs, [n for _, n in spans], levels, [t0 for t0, _ in spans], [0] * len(spans), dev)
+            st = torch.zeros(len(spans), dtype=torch.int32, device=dev)
+            e = time_reps(torch, stream, lambda: kvh.encode_batch(ei, len(spans), chunk, kv[0], kv[1], stream=stream), reps)
+            d = time_reps(torch, stream, lambda: kvh.decode_batch(di, len(spans), chunk, out[0], out[1], status=st, stream=stream), reps)
+            assert int(st.abs().sum().item()) == 0
+            rows.append({"bits": kvh.level_bits(level), "decode_batch": rate_fields(d, unc, blobs.numel()),
+                         "encode_batch": rate_fields(e, unc, blobs.numel())})
+            del blobs
+        res["llama3_70b_32k"] = {"workload": cfg.name, "chunks": N // chunk, "chunk_tokens": chunk,
+                                 "uncompressed_bytes": unc, "levels": rows}
+        del kv, out
+
+        # ---- 128K-token context, 256-token chunks: streamed and batched ----
+        cfg = gen.CONFIGS["long_7b_128k"]
+        l, N, c, chunk = cfg.l, cfg.n, cfg.c, cfg.chunk
+        kv = gen.make_kv_device(l, N, c, cfg.dtype, cfg.seed, device=dev)
+        out = torch.empty_like(kv)
+        unc = kv.numel() * 2
+        rows = []
+        for level in (0, 2):
+            spans, levels, sizes, offs = plan(l, N, c, chunk, lambda i: level)
+            blobs = torch.empty(int(sum(sizes)), dtype=torch.uint8, device=dev)
+            ptrs = [blobs.data_ptr() + int(o) for o in offs]
+            di = kvh.make_dec_items(ptrs, [n for _, n in spans], levels, [t0 for t0, _ in spans], [0] * len(spans), dev)
+            ei = kvh.make_enc_items(ptrs, [t0 for t0, _ in spans], [n for _, n in spans], levels, dev)
+            st = torch.zeros(len(spans), dtype=torch.int32, device=dev)
+            es = time_reps(torch, stream, lambda: kvh.encode_chunked(kv[0], kv[1], chunk, levels, blobs, offs, stream=stream), reps)
+            eb = time_reps(torch, stream, lambda: kvh.encode_batch(ei, len(spans), chunk, kv[0], kv[1], stream=stream), reps)
+            ds = time_reps(torch, stream, lambda: kvh.decode_chunked(blobs, offs, levels, chunk, N, out[0], out[1], status=st, stream=stream), reps)
+            db = time_reps(torch, stream, lambda: kvh.decode_batch(di, len(spans), chunk, out[0], out[1], status=st, stream=stream), reps)
+            assert int(st.abs().sum().item()) == 0
+            row = {"bits": kvh.level_bits(level), "decode_streamed": rate_fields(ds, unc, blobs.numel()),
+                   "decode_batch": rate_fields(db, unc, blobs.numel()),
+                   "encode_streamed": rate_fields(es, unc, blobs.numel()), "encode_batch": rate_fields(eb, unc, blobs.numel())}
+            row["decode_streamed"]["us_per_launch"] = ds["avg_ms"] * 1e3 / len(spans)
+            row["decode_streamed"]["launch_overhead_vs_batch"] = ds["avg_ms"] / db["avg_ms"] - 1.0
+            rows.append(row)
+            del blobs
+        res["long_7b_128k"] = {"workload": cfg.name, "chunks": N // chunk, "chunk_tokens": chunk, "uncompressed_bytes": unc,
+                               "streamed_form": "one kvh_decode launch per chunk (kvh_decode_chunked), one stream, one "
+                                                "synchronisation at the end", "levels": rows}
+        del kv, out
+
+        # ---- 64 requests of mixed lengths, a level per chunk, paged destination ----
+        dt, l, c, chunk, bt = gen.BF16, 32, 1024, 256, 16
+        lengths = gen.mixed_batch_lengths()
+        chunks, tables, n_pages = gen.mixed_batch_plan(lengths, chunk, bt)
+        total = int(lengths.sum())
+        starts = np.concatenate([[0], np.cumsum(lengths)[:-1]]).astype(np.int64)
+        kv = gen.make_kv_device(l, total, c, dt, seed=4, device=dev)
+        spans = [(int(starts[r] + t0), n) for r, t0, n, _ in chunks]
+        levels = [lv for _, _, _, lv in chunks]
+        sizes = [kvh.blob_size(l, n, c, lv) for (_, n), lv in zip(spans, levels)]
+        offs = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+        blobs = torch.empty(int(sum(sizes)), dtype=torch.uint8, device=dev)
+        ptrs = [blobs.data_ptr() + int(o) for o in offs]
+        ei = kvh.make_enc_items(ptrs, [t0 for t0, _ in spans], [n for _, n in spans], levels, dev)
+        e = time_reps(torch, stream, lambda: kvh.encode_batch(ei, len(spans), chunk, kv[0], kv[1], stream=stream), reps)
+        table_dev = torch.from_numpy(np.concatenate(tables)).to(dev)
+        table_start = np.concatenate([[0], np.cumsum([len(t) for t in tables])[:-1]])
+        paged = torch.empty((2, l, n_pages, bt, c), dtype=torch.bfloat16, device=dev)
+        st = torch.zeros(len(chunks), dtype=torch.int32, device=dev)
+        pi = kvh.make_dec_items(ptrs, [n for _, n in spans], levels, [t0 for _, t0, _, _ in chunks],
+                                [table_dev.data_ptr() + 4 * int(table_start[r]) for r, _, _, _ in chunks], dev)
+        ci = kvh.make_dec_items(ptrs, [n for _, n in spans], levels, [t0 for t0, _ in spans], [0] * len(spans), dev)
+        unc = kv.numel() * 2
+        dp = time_reps(torch, stream, lambda: kvh.decode_batch(pi, len(chunks), chunk, paged[0], paged[1], paged=True,
+                                                               block_tokens=bt, status=st, stream=stream), reps)
+        del paged
+        cont = torch.empty_like(kv)
+        dc = time_reps(torch, stream, lambda: kvh.decode_batch(ci, len(chunks), chunk, cont[0], cont[1], status=st, stream=stream), reps)
+        assert int(st.abs().sum().item()) == 0
+        res["mixed_batch_paged"] = {"workload": "mixed_64req_lognormal_mean4096_32x1024_bf16_paged16", "requests": len(lengths),
+                                    "tokens": total, "chunks": len(chunks), "chunk_tokens": chunk,
+                                    "chunks_per_level": [levels.count(i) for i in range(3)], "pages": n_pages, "block_tokens": bt,
+                                    "uncompressed_bytes": unc,
+                                    "decode_batch_paged": rate_fields(dp, unc, blobs.numel()),
+                                    "decode_batch_contiguous": rate_fields(dc, unc, blobs.numel()),
+                                    "encode_batch": rate_fields(e, unc, blobs.numel())}
+        del kv, cont, blobs
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -203,6 +400,27 @@ def main():
         pe[1].record(stream)
         torch.cuda.synchronize()
     copy_gbps = 5 * 2 * (1 << 30) / pe[0].elapsed_time(pe[1]) / 1e6
+    probes = None if args.no_extras else memory_probes(torch, kvh, stream, probe_src, probe_dst)
+
+    # Outside the timed region: the streamed forms of the same workload — one launch per chunk (kvh_encode_chunked /
+    # kvh_decode_chunked: 32 launches back to back on one stream, one synchronisation at the end), against the one
+    # batched launch the timed region uses.
+    streamed = []
+    if not args.no_extras:
+        with torch.cuda.stream(stream):
+            size_of = {lv: kvh.blob_size(l, chunk, c, lv) for lv in range(3)}
+            for level in range(3):
+                offs = [i * size_of[level] for i in range(n_chunks)]
+                lv = [level] * n_chunks
+                status[level].zero_()
+                d = time_reps(torch, stream, lambda: kvh.decode_chunked(blobs[level], offs, lv, chunk, N, out[0], out[1],
+                                                                        status=status[level], stream=stream), 10)
+                e = time_reps(torch, stream, lambda: kvh.encode_chunked(kv[0], kv[1], chunk, lv, blobs[level], offs,
+                                                                        stream=stream), 10)
+                assert int(status[level].abs().sum().item()) == 0
+                u_, b_ = 2 * l * N * c * 2, blobs[level].numel()
+                streamed.append({"bits": kvh.level_bits(level), "launches": n_chunks,
+                                 "decode_streamed": rate_fields(d, u_, b_), "encode_streamed": rate_fields(e, u_, b_)})
 
     # Also outside the timed region: the token-dropping method on the whole tensor as ONE entry of N tokens,
     # keeping sink = 128 and window = N/2 - 128 tokens (rate 1/2), stored at 8 and at 2 bits.
@@ -409,6 +627,7 @@ def main():
                           "elements_per_s": 2 * l * N * c / avg * 1e3,
                           "unfused_ms": by_op[("decode", ba)] + by_op[("encode", bb)]})
     dec2 = [r for r in per_kernel if r["op"] == "decode"]
+    others = None if args.no_extras else other_workloads(torch, np, gen, kvh, stream)
 
     result = {
         "metric": "KV decode & encode GB/s (uncompressed bytes) per level; % of HBM peak",
@@ -431,7 +650,12 @@ def main():
         "paper_context": "the paper reports no encode/decode throughput; its end-to-end figures (1.43-2.4x delay saving at "
                          "equal quality, 6-55 % quality gain at equal delay) are for 1x NVIDIA A100, 100 GB DRAM, 400 GB SSD "
                          "at 1 GB/s, Llama-3.1-8B-Instruct on 1,100 LongBench contexts: context, not a target for this metric",
+        "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, as recorded in "
+                          "profiles/codec_kernels_llama3_8b_8k_bf16.md (counters cannot be read inside this run)",
         "copy_probe_GBps": copy_gbps,
+        "memory_probes": probes,
+        "streamed_chunk_by_chunk": streamed,
+        "other_workloads": others,
         "token_dropping": dropping,
         "transcode": transcode,
         "load_path": load_path,

@@ -130,6 +130,16 @@ int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_
 int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, int level, const kvh_kv_view* dst,
                int64_t dst_token0, const int32_t* page_table_dev, int block_tokens, int32_t* status_dev, void* stream);
 
+/* Decompress a long entry chunk by chunk, streamed (the mirror of kvh_encode_chunked): chunk i holds tokens
+ * [i*chunk, min(N, (i+1)*chunk)), was stored at levels[i], starts at (char*)blobs_dev + blob_offsets[i] and goes to
+ * logical positions dst_token0 + i*chunk onward of `dst` (contiguous or paged, as kvh_decode).  `levels` and
+ * `blob_offsets` are HOST arrays of ceil(N/chunk) entries; offsets must be multiples of 16.  status_dev, if not
+ * NULL, has one zeroed int32 per chunk.  One kernel launch per chunk, all asynchronous on `stream`, no
+ * synchronisation in between: the first chunks can be consumed while later ones are still being decoded. */
+int kvh_decode_chunked(const void* blobs_dev, const size_t* blob_offsets, const int8_t* levels, kvh_dtype dt, int l, int N,
+                       int c, int chunk, const kvh_kv_view* dst, int64_t dst_token0, const int32_t* page_table_dev,
+                       int block_tokens, int32_t* status_dev, void* stream);
+
 /* One decode job of a batch.  The ARRAY of items lives in device memory. */
 typedef struct {
   const void* blob;          /* device pointer, 16-byte aligned */
@@ -331,6 +341,16 @@ int kvh_policy_plan(const kvh_policy_entry* entries, int n_entries, const double
  * aligned).  Not part of the codec: the benchmark uses it as the known-size reference that
  * scales the HBM byte counters and as the practical copy-bandwidth ceiling of the device. */
 int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* stream);
+
+/* Traffic generator with a chosen mix of reads and writes and no arithmetic, also not part of the codec: a unit is
+ * reads_per_unit x 16 bytes read per lane and writes_per_unit x 16 bytes written per lane (1 KiB per wave and
+ * access, non-temporal stores); n_units units (a multiple of 256) are processed, so src_dev must hold n_units * reads_per_unit * 16
+ * bytes and dst_dev n_units * writes_per_unit * 16 bytes (at least 16).  Supported (reads, writes): (1,0) pure
+ * read, (0,1) pure fill, (1,1) copy, (1,2) (1,4) (1,8) the decoder's mixes at 8 / 4 / 2 bits, (2,1) (4,1) (8,1)
+ * the encoder's; anything else is KVH_E_ARG.  The benchmark reports these next to the codec's kernels as the
+ * ceilings the memory system sets for such streams. */
+int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int reads_per_unit, int writes_per_unit,
+                     void* stream);
 
 /* Static description of a status code. */
 const char* kvh_strerror(int status);

@@ -106,6 +106,11 @@ def lib() -> ctypes.CDLL:
         L.kvh_policy_plan.argtypes = [vp, i32, vp, vp, i32, vp, i32, f64, vp, vp, ctypes.POINTER(f64)]
         L.kvh_copy_probe.restype = i32
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
+        L.kvh_stream_probe.restype = i32
+        L.kvh_stream_probe.argtypes = [vp, vp, sz, i32, i32, vp]
+        L.kvh_decode_chunked.restype = i32
+        L.kvh_decode_chunked.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_int8), i32, i32, i32, i32, i32,
+                                         view, i64, vp, i32, vp, vp]
         L.kvh_strerror.restype = ctypes.c_char_p
         L.kvh_strerror.argtypes = [i32]
         _lib = L
@@ -241,6 +246,30 @@ def decode(blob: torch.Tensor, level: int, n_tokens: int, k_dst: torch.Tensor, v
     _check(lib().kvh_decode(blob.data_ptr(), dt, l, n_tokens, c, level, ctypes.byref(view), dst_token0,
                             page_table.data_ptr() if paged else None, block_tokens,
                             status.data_ptr() if status is not None else None, _stream_ptr(stream)), "kvh_decode")
+
+
+def decode_chunked(blobs: torch.Tensor, blob_offsets, levels, chunk: int, n_tokens: int, k_dst: torch.Tensor,
+                   v_dst: torch.Tensor, dst_token0: int = 0, page_table: torch.Tensor | None = None,
+                   block_tokens: int = 16, status: torch.Tensor | None = None, stream=None) -> None:
+    """kvh_decode_chunked: one launch per chunk of an n_tokens entry whose blobs sit at the given byte offsets."""
+    paged = page_table is not None
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(blobs, page_table, status)
+    lv = np.ascontiguousarray(levels, dtype=np.int8)
+    off = np.ascontiguousarray(blob_offsets, dtype=np.uint64)
+    n_chunks = -(-n_tokens // chunk) if chunk > 0 else 0
+    if lv.size != n_chunks or off.size != n_chunks:
+        raise ValueError("levels and blob_offsets need ceil(N/chunk) entries")
+    if paged and page_table.dtype != torch.int32:
+        raise ValueError("page_table must be int32")
+    if status is not None and (status.dtype != torch.int32 or status.numel() < n_chunks):
+        raise ValueError("status must be int32 with one entry per chunk")
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_decode_chunked(blobs.data_ptr(), off.ctypes.data_as(ctypes.POINTER(ctypes.c_size_t)),
+                                    lv.ctypes.data_as(ctypes.POINTER(ctypes.c_int8)), dt, l, n_tokens, c, chunk,
+                                    ctypes.byref(view), dst_token0, page_table.data_ptr() if paged else None,
+                                    block_tokens, status.data_ptr() if status is not None else None,
+                                    _stream_ptr(stream)), "kvh_decode_chunked")
 
 
 def decode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int, k_dst: torch.Tensor,
@@ -385,6 +414,33 @@ def transcode_batch(items: torch.Tensor, n_items: int, max_tokens_per_item: int,
            "kvh_transcode_batch")
 
 
+def _load_items(host_blobs, n_tokens, levels, dst_token0, k_dst, v_dst, page_tables, status, drops):
+    """Marshal the HOST array of kvh_load_item shared by Loader.run and load_static."""
+    paged = page_tables is not None
+    view, dt = _view(k_dst, v_dst, paged)
+    _require_cuda(status)
+    n = len(host_blobs)
+    for b in host_blobs:
+        if b.is_cuda or not b.is_pinned() or b.dtype != torch.uint8:
+            raise ValueError("host blobs must be pinned uint8 host tensors")
+    if status is not None and (status.dtype != torch.int32 or status.numel() < n):
+        raise ValueError("status must be int32 with one entry per item")
+    a = np.zeros(n, dtype=LOAD_ITEM)
+    a["blob_host"] = [b.data_ptr() for b in host_blobs]
+    a["n_tokens"], a["level"], a["dst_token0"] = n_tokens, levels, dst_token0
+    if drops is not None:
+        for i, d in enumerate(drops):
+            if d is not None:
+                a["orig_tokens"][i], a["sink"][i], a["window"][i], a["compact"][i] = d[0], d[1], d[2], int(d[3])
+    if paged:
+        for t in page_tables:
+            _require_cuda(t)
+            if t.dtype != torch.int32:
+                raise ValueError("page tables must be int32")
+        a["page_table"] = [t.data_ptr() for t in page_tables]
+    return view, dt, a
+
+
 class Loader:
     """kvh_loader_*: blobs in pinned host memory -> staging slots in `staging` (uint8 device tensor) -> decode."""
 
@@ -407,28 +463,8 @@ class Loader:
             drops=None) -> None:
         """kvh_loader_run over pinned uint8 host tensors `host_blobs`; page_tables: int32 device tensors or None;
         drops: per blob None (ordinary) or (orig_tokens, sink, window, compact) for a token-dropped one."""
-        paged = page_tables is not None
-        view, dt = _view(k_dst, v_dst, paged)
-        _require_cuda(status)
+        view, dt, a = _load_items(host_blobs, n_tokens, levels, dst_token0, k_dst, v_dst, page_tables, status, drops)
         n = len(host_blobs)
-        for b in host_blobs:
-            if b.is_cuda or not b.is_pinned() or b.dtype != torch.uint8:
-                raise ValueError("host blobs must be pinned uint8 host tensors")
-        if status is not None and (status.dtype != torch.int32 or status.numel() < n):
-            raise ValueError("status must be int32 with one entry per item")
-        a = np.zeros(n, dtype=LOAD_ITEM)
-        a["blob_host"] = [b.data_ptr() for b in host_blobs]
-        a["n_tokens"], a["level"], a["dst_token0"] = n_tokens, levels, dst_token0
-        if drops is not None:
-            for i, d in enumerate(drops):
-                if d is not None:
-                    a["orig_tokens"][i], a["sink"][i], a["window"][i], a["compact"][i] = d[0], d[1], d[2], int(d[3])
-        if paged:
-            for t in page_tables:
-                _require_cuda(t)
-                if t.dtype != torch.int32:
-                    raise ValueError("page tables must be int32")
-            a["page_table"] = [t.data_ptr() for t in page_tables]
         l, c = k_dst.shape[0], k_dst.shape[-1]
         self._keep = (host_blobs, page_tables)  # the copies are asynchronous: keep the sources alive
         _check(lib().kvh_loader_run(self._h, a.ctypes.data, n, dt, l, c, ctypes.byref(view), block_tokens,
@@ -480,6 +516,17 @@ def policy_plan(freqs, sizes, qualities, alpha: float, tiers, min_choices=None):
                                  tr.ctypes.data, len(tiers), alpha, tier_out.ctypes.data, choice_out.ctypes.data,
                                  ctypes.byref(total)), "kvh_policy_plan")
     return tier_out, choice_out, total.value
+
+
+def stream_probe(dst: torch.Tensor, src: torch.Tensor, n_units: int, reads_per_unit: int, writes_per_unit: int,
+                 stream=None) -> None:
+    """kvh_stream_probe: traffic generator with a chosen read : write mix (no arithmetic)."""
+    _require_cuda(dst, src)
+    if src.numel() * src.element_size() < n_units * reads_per_unit * 16 or \
+            dst.numel() * dst.element_size() < max(16, n_units * writes_per_unit * 16):
+        raise ValueError("buffers too small for this many units")
+    _check(lib().kvh_stream_probe(dst.data_ptr(), src.data_ptr(), n_units, reads_per_unit, writes_per_unit,
+                                  _stream_ptr(stream)), "kvh_stream_probe")
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

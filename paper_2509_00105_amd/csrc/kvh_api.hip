@@ -29,6 +29,12 @@ int check_dst_view(const kvh_kv_view* v, int c) {
   return v->token_stride < c ? KVH_E_ARG : KVH_OK;
 }
 
+__device__ __forceinline__ void uintx4_nt_store(uint4* p, const uint4& v) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<__attribute__((address_space(1))) u32x4*>(reinterpret_cast<uintptr_t>(p)));
+}
+
 __global__ __launch_bounds__(kBlockThreads) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
                                                               size_t n16) {
   size_t i = (size_t)blockIdx.x * (kBlockThreads * 4) + threadIdx.x;
@@ -39,6 +45,52 @@ __global__ __launch_bounds__(kBlockThreads) void copy_kernel(uint4* __restrict__
 #pragma unroll
   for (int u = 0; u < 4; ++u)
     if (i + (size_t)u * kBlockThreads < n16) dst[i + (size_t)u * kBlockThreads] = r[u];
+}
+
+// Traffic generator with a chosen read : write mix and no arithmetic: a thread handles units of R 16-byte loads and
+// W 16-byte stores (each a full 1 KiB per wave), 4 units per thread.  What is stored depends on what was loaded, and
+// a pure read stream stores one word only under a condition that never holds, so no access can be optimised away.
+template <int R, int W>
+__global__ __launch_bounds__(kBlockThreads) void stream_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                                size_t n_units) {
+  constexpr int U = 4;
+  const size_t base = (size_t)blockIdx.x * (kBlockThreads * U);
+  uint4 acc = make_uint4(threadIdx.x, 1u, 2u, 3u);
+  uint4 r[U][R > 0 ? R : 1];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t unit = base + (size_t)u * kBlockThreads + threadIdx.x;
+    if (unit < n_units) {
+#pragma unroll
+      for (int j = 0; j < R; ++j) r[u][j] = src[(unit - threadIdx.x) * R + (size_t)j * kBlockThreads + threadIdx.x];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t unit = base + (size_t)u * kBlockThreads + threadIdx.x;
+    if (unit < n_units) {
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        acc.x ^= r[u][j].x; acc.y ^= r[u][j].y; acc.z ^= r[u][j].z; acc.w ^= r[u][j].w;
+      }
+#pragma unroll
+      for (int j = 0; j < W; ++j) {
+        uintx4_nt_store(&dst[(unit - threadIdx.x) * W + (size_t)j * kBlockThreads + threadIdx.x], acc);
+      }
+    }
+  }
+  if (W == 0 && (acc.x & acc.y & acc.z & acc.w) == 0xfffffffeu) dst[0] = acc;  // never true in practice: keeps the loads alive
+}
+
+template <int R, int W>
+int launch_stream(void* dst, const void* src, size_t n_units, hipStream_t stream) {
+  const size_t per_block = (size_t)kBlockThreads * 4;
+  const size_t blocks = (n_units + per_block - 1) / per_block;
+  if (blocks == 0 || blocks > 0x7fffffffu) return KVH_E_SIZE;
+  hipLaunchKernelGGL((stream_kernel<R, W>), dim3((unsigned)blocks), dim3(kBlockThreads), 0, stream,
+                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), n_units);
+  KVH_HIP_CHECK_LAUNCH();
+  return KVH_OK;
 }
 
 }  // namespace
@@ -152,6 +204,43 @@ int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, i
   a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
   a.split = kNoSplit;
   return launch_decode(a, dt, 1, n_tokens, static_cast<hipStream_t>(stream));
+}
+
+int kvh_decode_chunked(const void* blobs_dev, const size_t* blob_offsets, const int8_t* levels, kvh_dtype dt, int l, int N,
+                       int c, int chunk, const kvh_kv_view* dst, int64_t dst_token0, const int32_t* page_table_dev,
+                       int block_tokens, int32_t* status_dev, void* stream) {
+  if (blobs_dev == nullptr || blob_offsets == nullptr || levels == nullptr || (dt != KVH_F16 && dt != KVH_BF16) ||
+      dst_token0 < 0)
+    return KVH_E_ARG;
+  if (int rc = check_dst_view(dst, c)) return rc;
+  if (int rc = check_shape(l, N, c)) return rc;
+  if (chunk < kGroup || chunk % kGroup != 0) return KVH_E_SHAPE;
+  if (page_table_dev != nullptr && block_tokens < 1) return KVH_E_ARG;
+  if (dst_token0 + N > INT32_MAX) return KVH_E_ARG;
+  if (!aligned16(blobs_dev)) return KVH_E_ALIGN;
+  const int n_chunks = (N + chunk - 1) / chunk;
+  for (int i = 0; i < n_chunks; ++i) {  // validate everything before the first launch
+    if (level_bits(levels[i]) < 0) return KVH_E_LEVEL;
+    if (blob_offsets[i] % 16 != 0) return KVH_E_ALIGN;
+  }
+  DecodeParams a{};
+  a.items = nullptr;
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
+  a.split = kNoSplit;
+  for (int i = 0; i < n_chunks; ++i) {
+    const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
+    a.one = kvh_item{static_cast<const uint8_t*>(blobs_dev) + blob_offsets[i], n, levels[i],
+                     dst_token0 + (int64_t)i * chunk, page_table_dev};
+    a.status = status_dev != nullptr ? status_dev + i : nullptr;
+    if (int rc = launch_decode(a, dt, 1, n, static_cast<hipStream_t>(stream))) return rc;
+  }
+  return KVH_OK;
 }
 
 int kvh_decode_batch(const kvh_item* items_dev, int n_items, int max_tokens_per_item, kvh_dtype dt, int l, int c,
@@ -320,6 +409,26 @@ int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* strea
                      static_cast<uint4*>(dst_dev), static_cast<const uint4*>(src_dev), n16);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
+}
+
+int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int reads_per_unit, int writes_per_unit,
+                     void* stream) {
+  // whole groups of 256 units only: the j-th access of a group is laid out behind the (j-1)-th of all its threads
+  if (dst_dev == nullptr || src_dev == nullptr || n_units == 0 || n_units % kBlockThreads != 0) return KVH_E_ARG;
+  if (!aligned16(dst_dev) || !aligned16(src_dev)) return KVH_E_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (reads_per_unit * 16 + writes_per_unit) {
+    case 1 * 16 + 0: return launch_stream<1, 0>(dst_dev, src_dev, n_units, s);
+    case 0 * 16 + 1: return launch_stream<0, 1>(dst_dev, src_dev, n_units, s);
+    case 1 * 16 + 1: return launch_stream<1, 1>(dst_dev, src_dev, n_units, s);
+    case 1 * 16 + 2: return launch_stream<1, 2>(dst_dev, src_dev, n_units, s);
+    case 1 * 16 + 4: return launch_stream<1, 4>(dst_dev, src_dev, n_units, s);
+    case 1 * 16 + 8: return launch_stream<1, 8>(dst_dev, src_dev, n_units, s);
+    case 2 * 16 + 1: return launch_stream<2, 1>(dst_dev, src_dev, n_units, s);
+    case 4 * 16 + 1: return launch_stream<4, 1>(dst_dev, src_dev, n_units, s);
+    case 8 * 16 + 1: return launch_stream<8, 1>(dst_dev, src_dev, n_units, s);
+    default: return KVH_E_ARG;
+  }
 }
 
 const char* kvh_strerror(int status) {

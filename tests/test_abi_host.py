@@ -227,6 +227,33 @@ def test_transcode_default_output_is_device_memory_for_a_pinned_host_source(monk
     assert len(fake.calls) == 2
 
 
+def test_bench_traffic_figures_are_those_of_the_committed_profile(lib):
+    """bench.py reports HBM traffic per launch from the rocprofv3 summary under profiles/ (counters cannot be read
+    inside a run).  The parser must find all nine kernels there, and each figure must be what the table's own
+    counter columns give (2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE KiB) and sit within 10 % above the algorithmic bytes."""
+    import sys
+
+    sys.path.insert(0, ROOT)
+    import bench
+
+    got = bench.profiled_traffic()
+    want_keys = {("encode", b) for b in (8, 4, 2)} | {("decode", b) for b in (8, 4, 2)} | \
+                {("transcode", 8, 4), ("transcode", 8, 2), ("transcode", 4, 2)}
+    assert set(got) == want_keys
+    unc = 2 * 32 * 8192 * 1024 * 2
+    blob = {b: 32 * lib.kvh_blob_size(32, 256, 1024, lv) for lv, b in enumerate((8, 4, 2))}
+    for key, traffic in got.items():
+        alg = unc + blob[key[1]] if key[0] != "transcode" else blob[key[1]] + blob[key[2]]
+        assert alg <= traffic <= 1.10 * alg, (key, traffic, alg)
+    rows = [ln for ln in open(bench.PROFILE_SUMMARY).read().splitlines() if ln.startswith("| enc") or ln.startswith("| dec") or ln.startswith("| transcode")]
+    assert len(rows) == 9
+    for ln in rows:
+        cells = [x.strip() for x in ln.strip("|").split("|")]
+        fetch, write, traffic = int(cells[5]), int(cells[6]), int(cells[7])
+        assert traffic == (2 * fetch + write) * 1024, cells[0]
+    assert bench.profiled_traffic("/nonexistent/file.md") == {}
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The benchmark measures one GPU; asking for more must end with a message, before any GPU work."""
     import subprocess

@@ -217,11 +217,33 @@ def test_chunked_and_batched_encode_match_per_chunk_oracle(kvh):
     kvh.decode_batch(ditems, 4, chunk, ok, ov, status=status)
     torch.cuda.synchronize()
     assert not status.any()
+    # the streamed form: one launch per chunk from the same host arrays, at a token offset, contiguous and paged
+    base, bt = 32, 16
+    sk = torch.zeros((l, base + N + 7, c), dtype=torch.float16, device="cuda"); sv = torch.zeros_like(sk)
+    status.zero_()
+    kvh.decode_chunked(blobs2, offs, levels, chunk, N, sk, sv, dst_token0=base, status=status)
+    n_pages = -(-(base + N) // bt)
+    perm = np.random.default_rng(12).permutation(n_pages).astype(np.int32)
+    pk = torch.zeros((l, n_pages, bt, c), dtype=torch.float16, device="cuda"); pv = torch.zeros_like(pk)
+    kvh.decode_chunked(blobs2, offs, levels, chunk, N, pk, pv, dst_token0=base, page_table=torch.from_numpy(perm).cuda(),
+                       block_tokens=bt, status=status)
+    torch.cuda.synchronize()
+    assert not status.any()
+    inv = torch.from_numpy(perm.astype(np.int64)).cuda()
+    gk, gv = pk[:, inv].reshape(l, -1, c), pv[:, inv].reshape(l, -1, c)
     for i, lv in enumerate(levels):
         n = min(chunk, N - i * chunk)
         wk, wv = oracle.decode(want[i], dt, l, n, c, lv)
         assert_same_bits(to_host(ok[:, i * chunk:i * chunk + n]), wk, dt, "K chunk %d" % i)
         assert_same_bits(to_host(ov[:, i * chunk:i * chunk + n]), wv, dt, "V chunk %d" % i)
+        for what, tk, tv in (("streamed", sk, sv), ("streamed paged", gk, gv)):
+            assert_same_bits(to_host(tk[:, base + i * chunk:base + i * chunk + n]), wk, dt, "%s K chunk %d" % (what, i))
+            assert_same_bits(to_host(tv[:, base + i * chunk:base + i * chunk + n]), wv, dt, "%s V chunk %d" % (what, i))
+    assert not sk[:, :base].any() and not sk[:, base + N:].any()
+    with pytest.raises(kvh.KVHError):
+        kvh.decode_chunked(blobs2, offs, [2, 0, 1, 3], chunk, N, sk, sv)       # a level out of range: nothing launched
+    with pytest.raises(kvh.KVHError):
+        kvh.decode_chunked(blobs2, offs[:3], levels[:3], 320, N, sk, sv)        # chunk not a multiple of 128
 
 
 def test_header_mismatch_sets_status_and_writes_nothing(kvh):

@@ -160,12 +160,10 @@ def test_config4_long_context_streamed_decode(kvh):
         kvh.encode_chunked(kv[0], kv[1], chunk, levels, blobs, offs)       # one launch per chunk, one stream
         batched = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.empty_like(kv))
         streamed = torch.empty_like(kv)
-        status = torch.zeros(1, dtype=torch.int32, device="cuda")
-        for i, (t0, n) in enumerate(spans):                                 # chunk by chunk, never synchronising
-            kvh.decode(blobs[int(offs[i]):int(offs[i]) + sizes[i]], level, n, streamed[0], streamed[1], dst_token0=t0,
-                       status=status)
+        status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
+        kvh.decode_chunked(blobs, offs, levels, chunk, N, streamed[0], streamed[1], status=status)   # chunk by chunk, never synchronising
         torch.cuda.synchronize()
-        assert status.item() == 0
+        assert int(status.abs().sum().item()) == 0
         assert torch.equal(streamed.view(torch.int16), batched.view(torch.int16))
         seen = oracle_check_chunks(kv, streamed, blobs, picks, spans, levels, sizes, offs, dt, l, c)
         print("config 4, %d bits: oracle checked %d of %d chunks (every 4th, first, last)" % (kvh.level_bits(level), seen, n_chunks), flush=True)
