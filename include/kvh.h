@@ -301,6 +301,21 @@ int kvh_loader_run(kvh_loader* loader, const kvh_load_item* items, int n_items, 
 /* Wait for the loader's copies, then release its stream and events (not the staging buffer). */
 int kvh_loader_destroy(kvh_loader* loader);
 
+/* Allocation-free form of kvh_loader_run, for callers that cannot allocate or create anything: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same items, same checks, same result as
+ * kvh_loader_run, but there is no loader object, no second stream and no event: the one staging slot is a
+ * KVH_STATIC_SCRATCH_BYTES array inside the library's code object (every GPU the library runs on holds its own
+ * copy until the process ends), and each group of blobs is copied into it and decoded from it on `stream`, one
+ * after the other.  The call allocates and frees nothing (no hipMalloc/hipFree, no stream or event creation).
+ * The first call on a device looks up the array's address there and should be made outside any capture.
+ * A blob larger than KVH_STATIC_SCRATCH_BYTES - 1536 (the descriptor area) is refused with KVH_E_SIZE before
+ * anything is enqueued.  All calls on one GPU share that GPU's array, which keeps the last call's bytes; nothing
+ * in it has to start at zero.  Calls that overlap in time on one GPU (different streams, different threads)
+ * race on it: keep them on one stream, or order them yourself. */
+#define KVH_STATIC_SCRATCH_BYTES (40u << 20)
+int kvh_load_static(const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c, const kvh_kv_view* dst,
+                    int block_tokens, int32_t* status_dev, void* stream);
+
 /* ---- Storage policy (host only; no device work) -------------------------------------------------------
  * The paper's policy optimizer (Design section): Utility(i) = Freq(i) * (alpha * Quality(i, M_i, R_i) -
  * size(i, M_i, R_i) / Bandwidth); the marginal utility drop of going from rate m to rate n is

@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.kvh_loader_run.argtypes = [vp, vp, i32, i32, i32, i32, view, i32, vp, vp]
         L.kvh_loader_destroy.restype = i32
         L.kvh_loader_destroy.argtypes = [vp]
+        L.kvh_load_static.restype = i32
+        L.kvh_load_static.argtypes = [vp, i32, i32, i32, i32, view, i32, vp, vp]
         f64 = ctypes.c_double
         L.kvh_policy_utility.restype = f64
         L.kvh_policy_utility.argtypes = [f64] * 5
@@ -439,6 +441,20 @@ def _load_items(host_blobs, n_tokens, levels, dst_token0, k_dst, v_dst, page_tab
                 raise ValueError("page tables must be int32")
         a["page_table"] = [t.data_ptr() for t in page_tables]
     return view, dt, a
+
+
+STATIC_SCRATCH_BYTES = 40 << 20  # KVH_STATIC_SCRATCH_BYTES of include/kvh.h
+
+
+def load_static(host_blobs, n_tokens, levels, dst_token0, k_dst: torch.Tensor, v_dst: torch.Tensor, page_tables=None,
+                block_tokens: int = 16, status: torch.Tensor | None = None, stream=None, drops=None) -> None:
+    """kvh_load_static: Loader.run without a loader — one staging slot inside the library, nothing allocated.
+    The caller keeps `host_blobs` (and page tables) alive until the stream has been synchronised."""
+    view, dt, a = _load_items(host_blobs, n_tokens, levels, dst_token0, k_dst, v_dst, page_tables, status, drops)
+    l, c = k_dst.shape[0], k_dst.shape[-1]
+    _check(lib().kvh_load_static(a.ctypes.data, len(host_blobs), dt, l, c, ctypes.byref(view), block_tokens,
+                                 status.data_ptr() if status is not None else None, _stream_ptr(stream)),
+           "kvh_load_static")
 
 
 class Loader:

@@ -9,6 +9,7 @@
 // measured to leave 30-60 us of idle bus between two copies on this platform; with groups the
 // fixed costs are paid once per slot.  Two streams (copy, caller's compute) and two events per slot
 // order the ring; one more event orders a run's copies after what the caller's stream already holds.
+#include <mutex>
 #include <new>
 
 #include "kvh_common.hpp"
@@ -59,6 +60,93 @@ __global__ __launch_bounds__(kCopyThreads) void load_group_kernel(CopyGroup g, u
     for (int u = 0; u < kCopyUnroll; ++u)
       if (i + u * stride < n16) dst[i + u * stride] = r[u];
   }
+}
+
+
+// Everything kvh_loader_run and kvh_load_static check before they enqueue anything.  `capacity` = bytes a slot
+// offers to blobs.
+int validate_load(const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c, const kvh_kv_view* dst,
+                  int block_tokens, size_t capacity) {
+  if (items == nullptr || n_items < 1 || (dt != KVH_F16 && dt != KVH_BF16) || block_tokens < 1) return KVH_E_ARG;
+  if (dst == nullptr || dst->k == nullptr || dst->v == nullptr || dst->layer_stride < 0 || dst->token_stride < c)
+    return KVH_E_ARG;
+  if (((reinterpret_cast<uintptr_t>(dst->k) | reinterpret_cast<uintptr_t>(dst->v)) & 15u) != 0 ||
+      dst->layer_stride % 8 != 0 || dst->token_stride % 8 != 0)
+    return KVH_E_ALIGN;
+  for (int i = 0; i < n_items; ++i) {
+    const kvh_load_item& it = items[i];
+    if (it.blob_host == nullptr || it.dst_token0 < 0) return KVH_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(it.blob_host) & 15u) != 0) return KVH_E_ALIGN;
+    if (level_bits(it.level) < 0) return KVH_E_LEVEL;
+    const size_t need = kvh_blob_size(l, it.n_tokens, c, it.level);
+    if (need == 0) return KVH_E_SHAPE;
+    if (need > capacity) return KVH_E_SIZE;
+    // the copy kernel reads the blob in place: both ends must lie in host memory the device can see
+    const uint8_t* ends[2] = {static_cast<const uint8_t*>(it.blob_host), static_cast<const uint8_t*>(it.blob_host) + need - 1};
+    for (const uint8_t* p : ends) {
+      hipPointerAttribute_t at{};
+      if (hipPointerGetAttributes(&at, p) != hipSuccess || at.type != hipMemoryTypeHost) {
+        (void)hipGetLastError();
+        return KVH_E_ARG;
+      }
+    }
+    if ((it.orig_tokens | it.sink | it.window) != 0) {  // a token-dropped blob: n_tokens is what is kept
+      if (kvh_kept_tokens(it.orig_tokens, it.sink, it.window) != it.n_tokens) return KVH_E_SHAPE;
+    }
+    const int64_t span = (it.orig_tokens > it.n_tokens && !it.compact) ? it.orig_tokens : it.n_tokens;
+    if (it.dst_token0 + span > INT32_MAX) return KVH_E_ARG;
+  }
+  return KVH_OK;
+}
+
+// Pack consecutive blobs, starting at items[first], into one slot of `capacity` bytes for blobs; returns how many
+// went in (at least one: every blob has been checked against the capacity) and their largest token count.
+int pack_group(const kvh_load_item* items, int first, int n_items, int l, int c, uint8_t* slot, size_t capacity,
+               CopyGroup& g, int& max_tokens) {
+  size_t used = 0;
+  max_tokens = 0;
+  g.n = 0;
+  while (first + g.n < n_items && g.n < kMaxGroup) {
+    const kvh_load_item& it = items[first + g.n];
+    const size_t bytes = kvh_blob_size(l, it.n_tokens, c, it.level);
+    if (used + bytes > capacity) break;
+    g.src[g.n] = static_cast<const uint8_t*>(it.blob_host);
+    g.off[g.n] = kDescBytes + used;
+    g.n16[g.n] = bytes / 16;
+    g.item[g.n] = kvh_kept_item{slot + kDescBytes + used, it.n_tokens, it.level, it.dst_token0, it.page_table,
+                                it.orig_tokens, it.sink, it.window, it.compact};
+    if (it.n_tokens > max_tokens) max_tokens = it.n_tokens;
+    used += bytes;
+    ++g.n;
+  }
+  return g.n;
+}
+
+// ---- the allocation-free variant: its one staging slot lives in the code object -------------------------
+// Each device the library runs on holds its own copy of this array, at its own address, until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress; the address kernels and copies use is the one
+// that call returns, looked up once per device.
+static __device__ __align__(256) uint8_t scratch[KVH_STATIC_SCRATCH_BYTES];
+static_assert(KVH_STATIC_SCRATCH_BYTES % 256 == 0 && KVH_STATIC_SCRATCH_BYTES > kDescBytes + kHeaderBytes, "scratch size");
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+uint8_t* scratch_ptr[kMaxDevices];  // per device: address of `scratch` there, nullptr until first use
+
+// Address of the current device's scratch array (nullptr on failure).
+uint8_t* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    scratch_ptr[dev] = static_cast<uint8_t*>(p);
+  }
+  return scratch_ptr[dev];
 }
 
 }  // namespace
@@ -145,37 +233,8 @@ size_t kvh_loader_slot_bytes(const kvh_loader* ld) { return ld == nullptr ? 0 : 
 
 int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c,
                    const kvh_kv_view* dst, int block_tokens, int32_t* status_dev, void* stream) {
-  if (ld == nullptr || items == nullptr || n_items < 1 || (dt != KVH_F16 && dt != KVH_BF16) || block_tokens < 1)
-    return KVH_E_ARG;
-  if (dst == nullptr || dst->k == nullptr || dst->v == nullptr || dst->layer_stride < 0 || dst->token_stride < c)
-    return KVH_E_ARG;
-  if (((reinterpret_cast<uintptr_t>(dst->k) | reinterpret_cast<uintptr_t>(dst->v)) & 15u) != 0 ||
-      dst->layer_stride % 8 != 0 || dst->token_stride % 8 != 0)
-    return KVH_E_ALIGN;
-  // validate every item before anything is enqueued
-  for (int i = 0; i < n_items; ++i) {
-    const kvh_load_item& it = items[i];
-    if (it.blob_host == nullptr || it.dst_token0 < 0) return KVH_E_ARG;
-    if ((reinterpret_cast<uintptr_t>(it.blob_host) & 15u) != 0) return KVH_E_ALIGN;
-    if (level_bits(it.level) < 0) return KVH_E_LEVEL;
-    const size_t need = kvh_blob_size(l, it.n_tokens, c, it.level);
-    if (need == 0) return KVH_E_SHAPE;
-    if (need > ld->slot_bytes) return KVH_E_SIZE;
-    // the copy kernel reads the blob in place: both ends must lie in host memory the device can see
-    const uint8_t* ends[2] = {static_cast<const uint8_t*>(it.blob_host), static_cast<const uint8_t*>(it.blob_host) + need - 1};
-    for (const uint8_t* p : ends) {
-      hipPointerAttribute_t at{};
-      if (hipPointerGetAttributes(&at, p) != hipSuccess || at.type != hipMemoryTypeHost) {
-        (void)hipGetLastError();
-        return KVH_E_ARG;
-      }
-    }
-    if ((it.orig_tokens | it.sink | it.window) != 0) {  // a token-dropped blob: n_tokens is what is kept
-      if (kvh_kept_tokens(it.orig_tokens, it.sink, it.window) != it.n_tokens) return KVH_E_SHAPE;
-    }
-    const int64_t span = (it.orig_tokens > it.n_tokens && !it.compact) ? it.orig_tokens : it.n_tokens;
-    if (it.dst_token0 + span > INT32_MAX) return KVH_E_ARG;
-  }
+  if (ld == nullptr) return KVH_E_ARG;
+  if (int rc = validate_load(items, n_items, dt, l, c, dst, block_tokens, ld->slot_bytes)) return rc;
   hipStream_t compute = static_cast<hipStream_t>(stream);
   // Stream order: the copies read host blobs that work already enqueued on the caller's stream may
   // still be writing (an encode straight into pinned memory), so they start after that work.
@@ -192,25 +251,11 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
   a.split = kNoSplit;
   int first = 0;
   while (first < n_items) {
-    // pack consecutive blobs into one slot
     const int s = ld->next_slot;
     uint8_t* slot = ld->staging + (size_t)s * ld->slot_pitch;
     CopyGroup g{};
-    size_t used = 0;
     int max_tokens = 0;
-    while (first + g.n < n_items && g.n < kMaxGroup) {
-      const kvh_load_item& it = items[first + g.n];
-      const size_t bytes = kvh_blob_size(l, it.n_tokens, c, it.level);
-      if (used + bytes > ld->slot_bytes) break;
-      g.src[g.n] = static_cast<const uint8_t*>(it.blob_host);
-      g.off[g.n] = kDescBytes + used;
-      g.n16[g.n] = bytes / 16;
-      g.item[g.n] = kvh_kept_item{slot + kDescBytes + used, it.n_tokens, it.level, it.dst_token0, it.page_table,
-                                  it.orig_tokens, it.sink, it.window, it.compact};
-      if (it.n_tokens > max_tokens) max_tokens = it.n_tokens;
-      used += bytes;
-      ++g.n;
-    }
+    pack_group(items, first, n_items, l, c, slot, ld->slot_bytes, g, max_tokens);
     // the slot may still be read by the decode that used it last (in this run or an earlier one)
     if (ld->in_use[s] && hipStreamWaitEvent(ld->copy_stream, ld->freed[s], 0) != hipSuccess) return KVH_E_HIP;
     hipLaunchKernelGGL(load_group_kernel, dim3(kCopyBlocksPerBlob, (unsigned)g.n), dim3(kCopyThreads), 0,
@@ -224,6 +269,40 @@ int kvh_loader_run(kvh_loader* ld, const kvh_load_item* items, int n_items, kvh_
     if (hipEventRecord(ld->freed[s], compute) != hipSuccess) return KVH_E_HIP;
     ld->in_use[s] = true;
     ld->next_slot = (s + 1) % ld->n_slots;
+    first += g.n;
+  }
+  return KVH_OK;
+}
+
+int kvh_load_static(const kvh_load_item* items, int n_items, kvh_dtype dt, int l, int c, const kvh_kv_view* dst,
+                    int block_tokens, int32_t* status_dev, void* stream) {
+  constexpr size_t capacity = (size_t)KVH_STATIC_SCRATCH_BYTES - kDescBytes;
+  if (int rc = validate_load(items, n_items, dt, l, c, dst, block_tokens, capacity)) return rc;
+  uint8_t* slot = scratch_on_current_device();
+  if (slot == nullptr) return KVH_E_HIP;
+  hipStream_t compute = static_cast<hipStream_t>(stream);
+  DecodeParams a{};
+  a.k = static_cast<uint16_t*>(dst->k);
+  a.v = static_cast<uint16_t*>(dst->v);
+  a.layer_stride = dst->layer_stride;
+  a.token_stride = dst->token_stride;
+  a.l = l;
+  a.c = c;
+  a.block_tokens = block_tokens;
+  a.split = kNoSplit;
+  // One slot, one stream: copy group, decode group, copy the next group over it.  Stream order keeps a copy from
+  // overtaking the decode that still reads the slot; nothing in the slot has to start at zero (the copy kernel
+  // rewrites the descriptors of every group).
+  for (int first = 0; first < n_items;) {
+    CopyGroup g{};
+    int max_tokens = 0;
+    pack_group(items, first, n_items, l, c, slot, capacity, g, max_tokens);
+    hipLaunchKernelGGL(load_group_kernel, dim3(kCopyBlocksPerBlob, (unsigned)g.n), dim3(kCopyThreads), 0, compute, g,
+                       slot);
+    KVH_HIP_CHECK_LAUNCH();
+    a.kept_items = reinterpret_cast<const kvh_kept_item*>(slot);
+    a.status = status_dev != nullptr ? status_dev + first : nullptr;
+    if (int rc = launch_decode(a, dt, g.n, max_tokens, compute)) return rc;
     first += g.n;
   }
   return KVH_OK;
