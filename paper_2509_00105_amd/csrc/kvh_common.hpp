@@ -100,6 +100,17 @@ __device__ __forceinline__ T* uniform(T* p) {
   return reinterpret_cast<T*>(uniform((uint64_t)reinterpret_cast<uintptr_t>(p)));
 }
 
+// Load through the scalar data cache: for read-only data at a wave-uniform address (job descriptors, blob headers).
+// The result arrives in scalar registers after a much shorter round trip than a vector load's, and needs no
+// readfirstlane.  Only ever used for loads.
+#ifndef KVH_SCALAR_DESC
+#define KVH_SCALAR_DESC 1
+#endif
+template <typename T>
+__device__ __forceinline__ T sload(const void* p) {
+  return *reinterpret_cast<const __attribute__((address_space(4))) T*>(reinterpret_cast<uintptr_t>(p));
+}
+
 // ---- group parameters -------------------------------------------------------------------------
 // meta = mn | mx << 16 (raw 16-bit patterns as stored in the blob).
 struct GroupParams {

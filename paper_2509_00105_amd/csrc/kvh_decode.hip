@@ -23,14 +23,18 @@ namespace kvh {
 #ifndef KVH_DEC_NTL
 #define KVH_DEC_NTL 0  // non-temporal loads of the packed codes
 #endif
-constexpr int kDecWaves = 8;                                     // units per block
+#ifndef KVH_DEC_WAVES
+#define KVH_DEC_WAVES 8
+#endif
+constexpr int kDecWaves = KVH_DEC_WAVES;                         // units per block
 constexpr int kDecThreads = kDecWaves * kWave;
 constexpr int kDecSegs = 2;                                      // 512-channel segments per wave
 constexpr int kDecSpanCh = kDecSegs * kStripCh;                 // channels covered by one wave
 constexpr int kDecHeads = kDecSpanCh / kGroup;                  // V groups per row of a unit
 constexpr int kDecRows = kWave / kDecHeads;                     // token rows per wave: one lane per V group
 static_assert(kGroup % (kDecRows * kDecWaves) == 0, "a block must not straddle K token-groups");
-static_assert(kDecThreads * 2 == kDecSpanCh, "a thread prepares two K channels of the block's span");
+constexpr int kDecPrep = kDecSpanCh / kDecThreads;               // K channels of the block's span a thread prepares
+static_assert(kDecThreads * kDecPrep == kDecSpanCh && (kDecPrep == 2 || kDecPrep == 4), "K channels per thread");
 
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -145,8 +149,12 @@ __device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_t
 struct HeaderWords {
   uintx4 a, b, c;
 };
-__device__ __forceinline__ HeaderWords load_header(const uint8_t* blob) {
+__device__ __forceinline__ HeaderWords load_header(const uint8_t* blob) {  // blob is wave-uniform
+#if KVH_SCALAR_DESC
+  return {sload<uintx4>(blob), sload<uintx4>(blob + 16), sload<uintx4>(blob + 32)};
+#else
   return {gload<uintx4>(blob), gload<uintx4>(blob + 16), gload<uintx4>(blob + 32)};
+#endif
 }
 __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int bits, int l, int n, int c,
                                                size_t total, uint32_t orig_tokens, uint32_t sink, uint32_t window) {
@@ -201,11 +209,20 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   // V = group (row lane / H, head lane % H) of this unit
   uint32_t vm = 0;
   bool v_owner = false;
-  uintx2 kpair = {0u, 0u};
-  const int pc = span * kDecSpanCh + (int)threadIdx.x * 2;
-  const bool pact = !is_v && pc < c;
+  uint32_t kwords[kDecPrep] = {};
+  const int pc = span * kDecSpanCh + (int)threadIdx.x * kDecPrep;
+  const bool pact = !is_v && pc < c;  // c is a multiple of 128, so the thread's channels are all inside or all outside
   if (!is_v) {
-    if (pact) kpair = gload<uintx2>(kmeta + ((size_t)(t0_block / kGroup) * c + pc) * 4);
+    if (pact) {
+      const uint8_t* mp = kmeta + ((size_t)(t0_block / kGroup) * c + pc) * 4;
+      if constexpr (kDecPrep == 2) {
+        const uintx2 m = gload<uintx2>(mp);
+        kwords[0] = m.x; kwords[1] = m.y;
+      } else {
+        const uintx4 m = gload<uintx4>(mp);
+        kwords[0] = m.x; kwords[1] = m.y; kwords[2] = m.z; kwords[3] = m.w;
+      }
+    }
   } else {
     int t = t0 + lane / kDecHeads;
     int head = span * kDecHeads + lane % kDecHeads;
@@ -255,12 +272,11 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     GroupParams gp[kDecSegs][kLaneCh];
     bool fix = false;
     {
-      const uint32_t meta[2] = {kpair.x, kpair.y};
 #pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        GroupParams p = decode_params<DT, BITS>(meta[e]);
+      for (int e = 0; e < kDecPrep; ++e) {
+        GroupParams p = decode_params<DT, BITS>(kwords[e]);
         fix |= pact && top_needs_fix<DT, BITS>(p);
-        const int lc = (int)threadIdx.x * 2 + e;
+        const int lc = (int)threadIdx.x * kDecPrep + e;
         kshare[lc] = p.mn;
         kshare[kDecSpanCh + lc] = p.scale;
         kshare[2 * kDecSpanCh + lc] = __builtin_bit_cast(float, p.top);
@@ -306,13 +322,32 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
 template <int DT>
 __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
+#ifndef KVH_DEC_MAP
+#define KVH_DEC_MAP 1
+#endif
+#if KVH_DEC_MAP == 1
+  // planes fastest: consecutive blocks of the dispatch order take the same rows of consecutive (layer, K|V) planes
+  const int lin_xy = blockIdx.y * gridDim.x + blockIdx.x;
+  const int lay_kv = lin_xy % gridDim.y;
+  const int bx = lin_xy / gridDim.y;
+#elif KVH_DEC_MAP == 2
+  // K planes of all layers first, then V planes (rows fastest within a plane)
+  const int lay_kv = (blockIdx.y % (gridDim.y / 2)) * 2 + blockIdx.y / (gridDim.y / 2);
+  const int bx = blockIdx.x;
+#else
   const int lay_kv = blockIdx.y;
+  const int bx = blockIdx.x;
+#endif
   kvh_item it;
   DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
   bool consistent = true;
   if (a.items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
+#if KVH_SCALAR_DESC
+    uintx4 lo = sload<uintx4>(p), hi = sload<uintx4>(p + 16);
+#else
     uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16);
+#endif
     it.blob = reinterpret_cast<const void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
     it.n_tokens = (int32_t)lo.z;
     it.level = (int32_t)lo.w;
@@ -320,7 +355,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
     it.page_table = reinterpret_cast<const int32_t*>((uint64_t)hi.z | (uint64_t)hi.w << 32);
   } else if (a.kept_items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.kept_items + item_idx);
+#if KVH_SCALAR_DESC
+    uintx4 lo = sload<uintx4>(p), hi = sload<uintx4>(p + 16), ex = sload<uintx4>(p + 32);
+#else
     uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(p + 16), ex = gload<uintx4>(p + 32);
+#endif
     it.blob = reinterpret_cast<const void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
     it.n_tokens = (int32_t)lo.z;
     it.level = (int32_t)lo.w;
@@ -360,8 +399,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   __shared__ float kshare[3 * kDecSpanCh];  // K parameters of the block's span: minima, scales, top codes
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
-  const int strip = blockIdx.x % nspans;
-  const int t0_block = (blockIdx.x / nspans) * (kDecWaves * kDecRows);
+  const int strip = bx % nspans;
+  const int t0_block = (bx / nspans) * (kDecWaves * kDecRows);
   const int t0 = t0_block + wave * kDecRows;
   if (it.n_tokens < 1 || t0_block >= it.n_tokens) return;  // block-uniform
   const int lam = lay_kv >> 1;

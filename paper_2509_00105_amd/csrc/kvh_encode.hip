@@ -32,6 +32,29 @@ __device__ __forceinline__ void gstore(void* p, T v) {
   *reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)) = v;
 }
 
+#ifndef KVH_ENC_NT
+#define KVH_ENC_NT 1  // non-temporal stores of the packed codes
+#endif
+#ifndef KVH_ENC_NTL
+#define KVH_ENC_NTL 1  // non-temporal loads of the 16-bit rows
+#endif
+template <typename T>
+__device__ __forceinline__ T gload_rows(const void* p) {
+#if KVH_ENC_NTL
+  return __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void gstore_codes(void* p, T v) {
+#if KVH_ENC_NT
+  __builtin_nontemporal_store(v, reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  gstore<T>(p, v);
+#endif
+}
+
 template <int DT>
 __device__ __forceinline__ void unpack8(const uintx4& d, float (&x)[8]) {
   const uint32_t w[4] = {d.x, d.y, d.z, d.w};
@@ -89,11 +112,11 @@ __device__ __forceinline__ void quantise_store8(uint8_t* p, const float (&x)[8],
   for (int j = 0; j < 8; ++j) t[j] = position(x[j], param(j).x, param(j).y);
   if constexpr (BITS == 8) {
     uintx2 w = {codes4(t[0], t[1], t[2], t[3]), codes4(t[4], t[5], t[6], t[7])};
-    gstore<uintx2>(p, w);
+    gstore_codes<uintx2>(p, w);
   } else if constexpr (BITS == 4) {
-    gstore<uint32_t>(p, codes4(t[0], t[2], t[4], t[6]) | codes4(t[1], t[3], t[5], t[7]) << 4);
+    gstore_codes<uint32_t>(p, codes4(t[0], t[2], t[4], t[6]) | codes4(t[1], t[3], t[5], t[7]) << 4);
   } else {
-    gstore<uint16_t>(p, (uint16_t)(codes2(t[0], t[4]) | codes2(t[1], t[5]) << 2 | codes2(t[2], t[6]) << 4 |
+    gstore_codes<uint16_t>(p, (uint16_t)(codes2(t[0], t[4]) | codes2(t[1], t[5]) << 2 | codes2(t[2], t[6]) << 4 |
                                    codes2(t[3], t[7]) << 6));
   }
 }
@@ -119,7 +142,7 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
   for (int i = 0; i < kEncRows; ++i) {
     int t = t_first + i;
     t = t < n ? t : n - 1;
-    d[i] = gload<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
+    d[i] = gload_rows<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
   }
   float mn[8], mx[8];
   unpack8<DT>(d[0], mn);
@@ -249,7 +272,7 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
     for (int i = 0; i < kEncRows; ++i) {
       int t = t_first + i;
       t = t < n ? t : n - 1;
-      d[i] = gload<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
+      d[i] = gload_rows<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
     }
 #pragma unroll
     for (int i = 0; i < kEncRows; ++i) {
@@ -287,6 +310,7 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
   }
 }
 
+
 // grid = (token-groups x strips, 2 * l, items)
 template <int DT>
 __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void encode_kernel(EncodeParams a) {
@@ -295,15 +319,24 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
   if (a.items != nullptr) {
     const kvh_enc_item* p = a.items + blockIdx.z;
+#if KVH_SCALAR_DESC
+    uintx4 lo = sload<uintx4>(p);
+    uintx2 hi = sload<uintx2>(reinterpret_cast<const uint8_t*>(p) + 16);
+#else
     uintx4 lo = gload<uintx4>(p);
     uintx2 hi = gload<uintx2>(reinterpret_cast<const uint8_t*>(p) + 16);
+#endif
     it.blob = reinterpret_cast<void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
     it.src_token0 = (int64_t)((uint64_t)lo.z | (uint64_t)lo.w << 32);
     it.n_tokens = (int32_t)hi.x;
     it.level = (int32_t)hi.y;
   } else if (a.kept_items != nullptr) {
     const kvh_kept_enc_item* p = a.kept_items + blockIdx.z;
+#if KVH_SCALAR_DESC
+    uintx4 lo = sload<uintx4>(p), hi = sload<uintx4>(reinterpret_cast<const uint8_t*>(p) + 16);
+#else
     uintx4 lo = gload<uintx4>(p), hi = gload<uintx4>(reinterpret_cast<const uint8_t*>(p) + 16);
+#endif
     it.blob = reinterpret_cast<void*>((uint64_t)lo.x | (uint64_t)lo.y << 32);
     it.src_token0 = (int64_t)((uint64_t)lo.z | (uint64_t)lo.w << 32);
     const int32_t orig = uniform((int32_t)hi.x), sink = uniform((int32_t)hi.y), window = uniform((int32_t)hi.z);
@@ -329,18 +362,30 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   const int split = drop.split;
   const int64_t jump = drop.jump;
   const int nstrips = (a.c + kStripCh - 1) / kStripCh;
-  const int tile = blockIdx.x / nstrips;
-  const int strip = blockIdx.x - tile * nstrips;
+#ifndef KVH_ENC_MAP
+#define KVH_ENC_MAP 1
+#endif
+#if KVH_ENC_MAP == 1
+  // planes fastest: consecutive blocks of the dispatch order take the same tile of consecutive (layer, K|V) planes
+  const int lin_xy = blockIdx.y * gridDim.x + blockIdx.x;
+  const int lay_kv = lin_xy % gridDim.y;
+  const int bx = lin_xy / gridDim.y;
+#else
+  const int lay_kv = blockIdx.y;
+  const int bx = blockIdx.x;
+#endif
+  const int tile = bx / nstrips;
+  const int strip = bx - tile * nstrips;
   const int bits = level_bits(it.level);
   // block-uniform; an item with more tokens than the grid covers is skipped as a whole (no header either), so
   // that a later decode of its blob reports a mismatch instead of reading sections that were never written
   if (bits < 0 || it.n_tokens < 1 || it.n_tokens > a.max_tokens || tile * kEncTile >= it.n_tokens) return;
   const LayerGeom geo = layer_geom(it.n_tokens, a.c, bits);
   uint8_t* blob = static_cast<uint8_t*>(it.blob);
-  const int lam = blockIdx.y >> 1;
-  const bool is_v = blockIdx.y & 1;
+  const int lam = lay_kv >> 1;
+  const bool is_v = lay_kv & 1;
 
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < kHeaderBytes / 4) {
+  if (bx == 0 && lay_kv == 0 && threadIdx.x < kHeaderBytes / 4) {
     const uint64_t total = kHeaderBytes + (uint64_t)a.l * geo.layer_bytes();
     uint32_t w = 0;
     switch (threadIdx.x) {

@@ -60,6 +60,17 @@ template <typename T>
 __device__ __forceinline__ T gload(const uint8_t* p) {
   return *reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p));
 }
+#ifndef KVH_TC_NTL
+#define KVH_TC_NTL 1  // non-temporal loads of the input codes
+#endif
+template <typename T>
+__device__ __forceinline__ T gload_codes(const uint8_t* p) {
+#if KVH_TC_NTL
+  return __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  return gload<T>(p);
+#endif
+}
 template <typename T>
 __device__ __forceinline__ void gstore(uint8_t* p, T v) {
   *reinterpret_cast<__attribute__((address_space(1))) T*>(reinterpret_cast<uintptr_t>(p)) = v;
@@ -104,7 +115,7 @@ struct InCodes;
 template <>
 struct InCodes<8> {
   uintx4 w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx4>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_codes<uintx4>(p); }
   __device__ __forceinline__ float get(const uint32_t (&e)[4], int j) const { return (float)((e[j >> 2] >> (8 * (j & 3))) & 0xffu); }
   __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
     e[0] = w.x; e[1] = w.y; e[2] = w.z; e[3] = w.w;
@@ -113,7 +124,7 @@ struct InCodes<8> {
 template <>
 struct InCodes<4> {
   uintx2 w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uintx2>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_codes<uintx2>(p); }
   // e[0] / e[1] = even / odd nibbles of the first word, e[2] / e[3] of the second
   __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
     e[0] = opaque(w.x & 0x0f0f0f0fu);
@@ -128,7 +139,7 @@ struct InCodes<4> {
 template <>
 struct InCodes<2> {
   uint32_t w;
-  __device__ __forceinline__ void load(const uint8_t* p) { w = gload<uint32_t>(p); }
+  __device__ __forceinline__ void load(const uint8_t* p) { w = gload_codes<uint32_t>(p); }
   // e[k] holds codes k, k + 4, k + 8, k + 12 in its four bytes
   __device__ __forceinline__ void spread(uint32_t (&e)[4]) const {
 #pragma unroll
