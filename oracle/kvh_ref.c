@@ -31,6 +31,10 @@
  *               kept token i back at its original position, or at position i (compact).
  *   blob        64-byte header, then per layer: kmeta | kcodes | vmeta | vcodes, every section
  *               padded to a multiple of 16 bytes.
+ *   raw level   level 3 stores an entry in full quality (one of the three choices the policy's greedy step has
+ *               for an entry: evict, store in full quality, compress; Design section): b = 16, no groups, no
+ *               metadata; per layer the n K rows and then the n V rows, every 16-bit pattern kept as it is
+ *               (non-finite values included); header as above with bits = 16.
  */
 #include <math.h>
 #include <stddef.h>
@@ -110,13 +114,14 @@ uint16_t kvh_ref_f32_to_t16(float f, int dt) {
 /* ------------------------------------------------------------------------------------------
  * Level table and blob geometry.
  * ---------------------------------------------------------------------------------------- */
-int kvh_ref_num_levels(void) { return 3; }
+int kvh_ref_num_levels(void) { return 3; } /* the quantised levels 0..2; level 3 is the raw one */
 
 int kvh_ref_level_bits(int level) {
   switch (level) {
     case 0: return 8;
     case 1: return 4;
     case 2: return 2;
+    case 3: return 16; /* full quality: rows stored as they are */
     default: return -1;
   }
 }
@@ -126,9 +131,12 @@ static size_t pad16(size_t x) { return (x + 15u) & ~(size_t)15u; }
 static int shape_ok(int l, int n, int c) { return l >= 1 && n >= 1 && c >= REF_GROUP && c % REF_GROUP == 0; }
 
 /* section sizes of one layer */
-static size_t kmeta_bytes(int n, int c) { return pad16((size_t)((n + REF_GROUP - 1) / REF_GROUP) * (size_t)c * 4u); }
+static size_t kmeta_bytes_q(int n, int c) { return pad16((size_t)((n + REF_GROUP - 1) / REF_GROUP) * (size_t)c * 4u); }
 static size_t codes_bytes(int n, int c, int bits) { return pad16((size_t)n * ((size_t)c * (size_t)bits / 8u)); }
-static size_t vmeta_bytes(int n, int c) { return pad16((size_t)n * (size_t)(c / REF_GROUP) * 4u); }
+static size_t vmeta_bytes_q(int n, int c) { return pad16((size_t)n * (size_t)(c / REF_GROUP) * 4u); }
+/* the raw level has no groups and therefore no metadata sections */
+#define kmeta_bytes(n, c) (bits == 16 ? (size_t)0 : kmeta_bytes_q(n, c))
+#define vmeta_bytes(n, c) (bits == 16 ? (size_t)0 : vmeta_bytes_q(n, c))
 
 size_t kvh_ref_blob_size(int l, int n, int c, int level) {
   int bits = kvh_ref_level_bits(level);
@@ -239,7 +247,7 @@ int kvh_ref_encode(const uint16_t* k, const uint16_t* v, int64_t layer_stride, i
   size_t total = kvh_ref_blob_size(l, n, c, level);
   if (blob_cap < total) return KVH_REF_E_SIZE;
 
-  const int per_byte = 8 / bits;
+  const int per_byte = bits == 16 ? 1 : 8 / bits;
   const size_t row_bytes = (size_t)c * (size_t)bits / 8u;
   const int n_groups = (n + REF_GROUP - 1) / REF_GROUP;
   int nonfinite = 0;
@@ -256,6 +264,15 @@ int kvh_ref_encode(const uint16_t* k, const uint16_t* v, int64_t layer_stride, i
     uint8_t* vmeta = kcodes + codes_bytes(n, c, bits);
     uint8_t* vcodes = vmeta + vmeta_bytes(n, c);
     p = vcodes + codes_bytes(n, c, bits);
+
+    if (bits == 16) { /* full quality: the rows as they are, K then V */
+      for (int t = 0; t < n; ++t)
+        for (int ch = 0; ch < c; ++ch) {
+          put_u16(kcodes + ((size_t)t * c + ch) * 2, K[(int64_t)t * token_stride + ch]);
+          put_u16(vcodes + ((size_t)t * c + ch) * 2, V[(int64_t)t * token_stride + ch]);
+        }
+      continue;
+    }
 
     /* K: one group per (token-group, channel), statistics over tokens */
     for (int g = 0; g < n_groups; ++g) {
@@ -333,6 +350,13 @@ int kvh_ref_decode(const uint8_t* blob, size_t blob_len, int dt, int l, int n, i
       int64_t row = page_table ? (int64_t)page_table[s / block_tokens] * block_tokens + s % block_tokens : s;
       uint16_t* krow = kdst + (int64_t)lam * layer_stride + row * token_stride;
       uint16_t* vrow = vdst + (int64_t)lam * layer_stride + row * token_stride;
+      if (bits == 16) { /* full quality: the stored rows as they are */
+        for (int ch = 0; ch < c; ++ch) {
+          krow[ch] = get_u16(kcodes + ((size_t)t * c + ch) * 2);
+          vrow[ch] = get_u16(vcodes + ((size_t)t * c + ch) * 2);
+        }
+        continue;
+      }
       for (int ch = 0; ch < c; ++ch) {
         const uint8_t* km = kmeta + ((size_t)(t / REF_GROUP) * c + ch) * 4;
         const uint8_t* vm = vmeta + ((size_t)t * (c / REF_GROUP) + ch / REF_GROUP) * 4;

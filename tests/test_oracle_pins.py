@@ -261,7 +261,7 @@ def test_embedding_offsets_typed_by_hand():
 # ---------------------------------------------------------------------------------------------
 def test_levels_and_blob_size_closed_form():
     assert oracle.num_levels() == 3
-    assert [oracle.level_bits(i) for i in (-1, 0, 1, 2, 3)] == [-1, 8, 4, 2, -1]
+    assert [oracle.level_bits(i) for i in (-1, 0, 1, 2, 3, 4)] == [-1, 8, 4, 2, 16, -1]  # 3 = the raw level
     # a 256-token chunk of the 32-layer, 1024-channel shape: 64 + l*(ceil(n/128)*4c + n*4c/128 + 2*n*c*b/8)
     assert [oracle.blob_size(32, 256, 1024, lv) for lv in range(3)] == [17_301_568, 8_912_960, 4_718_656]
     U = 2 * 32 * 256 * 1024 * 2
@@ -274,7 +274,7 @@ def test_levels_and_blob_size_closed_form():
         pad = lambda x: (x + 15) // 16 * 16
         want = 64 + l * (-(-n // 128) * 4 * c + pad(n * 4 * c // 128) + 2 * n * c * b // 8)
         assert oracle.blob_size(l, n, c, lv) == want
-    for bad in [(0, 1, 128, 0), (1, 0, 128, 0), (1, 1, 64, 0), (1, 1, 192, 0), (1, 1, 128, 3), (1, 1, 128, -1)]:
+    for bad in [(0, 1, 128, 0), (1, 0, 128, 0), (1, 1, 64, 0), (1, 1, 192, 0), (1, 1, 128, 4), (1, 1, 128, -1)]:
         assert oracle.blob_size(*bad) == 0
 
 
