@@ -295,7 +295,7 @@ def test_error_paths():
     k, v = gen.make_kv(1, 128, 128, F16, 1)
     good = oracle.encode(k, v, F16, 1)
     blob = np.zeros(good.size, dtype=np.uint8)
-    assert oracle.encode_rc(k, v, F16, 3, blob) == oracle.E_LEVEL
+    assert oracle.encode_rc(k, v, F16, 4, blob) == oracle.E_LEVEL
     assert oracle.encode_rc(k, v, 2, 1, blob) == oracle.E_ARG
     assert oracle.encode_rc(k[:, :, :64], v[:, :, :64], F16, 1, blob) == oracle.E_SHAPE
     assert oracle.encode_rc(k, v, F16, 1, blob[:-1]) == oracle.E_SIZE
