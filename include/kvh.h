@@ -24,6 +24,11 @@
  *   then for each layer:  kmeta[ceil(n/128)][c]{mn,mx}  kcodes[n][c*b/8]
  *                         vmeta[n][c/128]{mn,mx}        vcodes[n][c*b/8]
  *   each section padded with zero bytes to a multiple of 16.
+ *   Level 3 (KVH_LEVEL_RAW) stores an entry in full quality — the paper's greedy step chooses per entry between
+ *   evicting it, storing it in full quality and compressing it (Design section): bits = 16 in the header, no
+ *   groups and no metadata sections, per layer the n K rows and then the n V rows exactly as given (every bit
+ *   pattern is kept, non-finite values included).  Encode, decode, the token-dropping calls and the loader take
+ *   it like any other level (token dropping at this level is dropping alone, without quantisation).
  *
  * Conventions
  *   - Pointers named *_dev are DEVICE pointers owned by the caller; everything else is host
@@ -56,7 +61,7 @@ typedef enum { KVH_F16 = 0, KVH_BF16 = 1 } kvh_dtype;
 typedef enum {
   KVH_OK = 0,
   KVH_E_ARG = -1,   /* null pointer, bad dtype, negative offset, bad block_tokens, too many items */
-  KVH_E_LEVEL = -2, /* level outside 0..2 */
+  KVH_E_LEVEL = -2, /* level outside 0..3, or the raw level passed to a call that only takes quantised levels */
   KVH_E_SHAPE = -3, /* l < 1, n < 1, c not a positive multiple of 128, chunk not a multiple of 128 */
   KVH_E_SIZE = -4,  /* blob capacity too small */
   KVH_E_ALIGN = -5, /* a base pointer or stride breaks the 16-byte rule */
@@ -66,9 +71,11 @@ typedef enum {
 /* Value written to *status_dev by a decode kernel whose blob header disagrees with the call. */
 #define KVH_DEV_HEADER_MISMATCH 1
 
-/* The level table (reading of the paper's Level k, its compression rate): 3 levels. */
+/* The level table (reading of the paper's Level k, its compression rate): 3 quantised levels, 0..2, and the
+ * raw level below them in the numbering. */
 int kvh_num_levels(void);
-/* Bits per element of a level: 0,1,2 -> 8,4,2; anything else -> -1. */
+#define KVH_LEVEL_RAW 3
+/* Bits per element of a level: 0,1,2 -> 8,4,2; KVH_LEVEL_RAW -> 16; anything else -> -1. */
 int kvh_level_bits(int level);
 /* Exact size in bytes of a blob holding n_tokens tokens; 0 on bad arguments.  This is the
  * size(i, M_i, R_i) term of the paper's utility for the quantisation method. */
@@ -231,8 +238,11 @@ int kvh_decode_kept_batch(const kvh_kept_item* items_dev, int n_items, int max_t
  * Precondition: the source blob was written by this library (encode, encode_kept or transcode), so that
  * every group holds its smallest and largest code; a hand-made blob without that property gets the
  * source's group statistics instead of recomputed ones.  Token-dropping header words are carried over.
- * Source and destination must not overlap.  Any pair of levels is allowed (going up only re-packs what
- * the lower level kept). */
+ * Source and destination must not overlap.  Any pair of quantised levels is allowed (going up only re-packs
+ * what the lower level kept).  The raw level is refused here (KVH_E_LEVEL; in a batch: KVH_DEV_HEADER_MISMATCH):
+ * a raw blob holds rows, not codes, so compressing it further is kvh_encode on a view of its rows (K rows of
+ * layer j start at byte 64 + j * 4 n c, the V rows 2 n c bytes later: k = blob + 64, v = blob + 64 + 2 n c,
+ * layer_stride = 2 n c elements, token_stride = c), and expanding a quantised blob to it is kvh_decode. */
 
 /* The kernel checks the source header against (dt, l, n_tokens, c, level_in) — n_tokens is the number
  * of tokens stored in the blob — and on disagreement writes KVH_DEV_HEADER_MISMATCH to *status_dev (if

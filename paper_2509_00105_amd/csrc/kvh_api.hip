@@ -333,6 +333,7 @@ int kvh_transcode(const void* src_dev, kvh_dtype dt, int l, int n_tokens, int c,
                   void* dst_dev, size_t dst_cap, int32_t* status_dev, void* stream) {
   if (src_dev == nullptr || dst_dev == nullptr || (dt != KVH_F16 && dt != KVH_BF16)) return KVH_E_ARG;
   if (level_bits(level_in) < 0 || level_bits(level_out) < 0) return KVH_E_LEVEL;
+  if (level_in == kRawLevel || level_out == kRawLevel) return KVH_E_LEVEL;  // raw blobs hold rows, not codes
   if (int rc = check_shape(l, n_tokens, c)) return rc;
   const size_t size_in = kvh_blob_size(l, n_tokens, c, level_in), size_out = kvh_blob_size(l, n_tokens, c, level_out);
   if (dst_cap < size_out) return KVH_E_SIZE;
@@ -435,7 +436,7 @@ const char* kvh_strerror(int status) {
   switch (status) {
     case KVH_OK: return "ok";
     case KVH_E_ARG: return "bad argument (null pointer, dtype, offset, block size or item count)";
-    case KVH_E_LEVEL: return "level outside 0..2";
+    case KVH_E_LEVEL: return "level outside 0..3 (or the raw level where only quantised levels are allowed)";
     case KVH_E_SHAPE: return "bad shape (l, n >= 1; c and chunk multiples of 128)";
     case KVH_E_SIZE: return "blob capacity too small";
     case KVH_E_ALIGN: return "pointer or stride breaks the 16-byte alignment rule";

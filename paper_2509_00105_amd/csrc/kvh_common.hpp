@@ -45,7 +45,10 @@ constexpr int kBlockThreads = 256; // 4 waves
 constexpr int kWavesPerBlock = kBlockThreads / kWave;
 constexpr uint32_t kMagic = 0x3148564Bu;  // "KVH1" read as a little-endian u32
 
-__host__ __device__ inline int level_bits(int level) { return level == 0 ? 8 : level == 1 ? 4 : level == 2 ? 2 : -1; }
+constexpr int kRawLevel = 3;  // full quality: 16 bits per element, rows stored as they are, no metadata
+__host__ __device__ inline int level_bits(int level) {
+  return level == 0 ? 8 : level == 1 ? 4 : level == 2 ? 2 : level == kRawLevel ? 16 : -1;
+}
 __host__ __device__ inline size_t pad16(size_t x) { return (x + 15) & ~size_t(15); }
 
 // Byte sizes of the four sections of one layer.
@@ -58,9 +61,9 @@ struct LayerGeom {
 __host__ __device__ inline LayerGeom layer_geom(int n, int c, int bits) {
   LayerGeom g;
   g.row_bytes = size_t(c) * bits / 8;
-  g.kmeta = pad16(size_t((n + kGroup - 1) / kGroup) * c * 4);
+  g.kmeta = bits == 16 ? 0 : pad16(size_t((n + kGroup - 1) / kGroup) * c * 4);  // the raw level has no groups
   g.codes = pad16(size_t(n) * g.row_bytes);
-  g.vmeta = pad16(size_t(n) * (c / kGroup) * 4);
+  g.vmeta = bits == 16 ? 0 : pad16(size_t(n) * (c / kGroup) * 4);
   return g;
 }
 

@@ -32,9 +32,14 @@ constexpr int kDecSegs = 2;                                      // 512-channel 
 constexpr int kDecSpanCh = kDecSegs * kStripCh;                 // channels covered by one wave
 constexpr int kDecHeads = kDecSpanCh / kGroup;                  // V groups per row of a unit
 constexpr int kDecRows = kWave / kDecHeads;                     // token rows per wave: one lane per V group
-static_assert(kGroup % (kDecRows * kDecWaves) == 0, "a block must not straddle K token-groups");
+#ifndef KVH_DEC_SUB
+#define KVH_DEC_SUB 1
+#endif
+constexpr int kDecSub = KVH_DEC_SUB;                            // units a wave decodes one after the other
+constexpr int kDecBlockRows = kDecRows * kDecSub * kDecWaves;   // token rows per block
+static_assert(kGroup % kDecBlockRows == 0, "a block must not straddle K token-groups");
 constexpr int kDecPrep = kDecSpanCh / kDecThreads;               // K channels of the block's span a thread prepares
-static_assert(kDecThreads * kDecPrep == kDecSpanCh && (kDecPrep == 2 || kDecPrep == 4), "K channels per thread");
+static_assert(kDecThreads * kDecPrep == kDecSpanCh && (kDecPrep == 1 || kDecPrep == 2 || kDecPrep == 4), "K channels per thread");
 
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
@@ -164,13 +169,14 @@ __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int
          h.c.y == sink && h.c.z == window;
 }
 
-// One unit: every load the unit needs (header, page-table entries, metadata, codes) is issued
-// up front so that their latencies overlap; the header verdict is taken before anything is
-// stored.  The caller guarantees kvh_blob_size(l, n_tokens, c, level) readable bytes at the
-// blob pointer, so these loads stay inside the buffer whatever the header says.
+// One wave's share of a block: kDecSub units of kDecRows consecutive rows each, one after the other.  Every load a
+// unit needs (page-table entries, metadata, codes; for the first unit also the header) is issued up front so that
+// their latencies overlap; the header verdict is taken before anything is stored.  The caller guarantees
+// kvh_blob_size(l, n_tokens, c, level) readable bytes at the blob pointer, so these loads stay inside the buffer
+// whatever the header says.
 template <int DT, int BITS>
 __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
-                                            int t0, int span, float* kshare, int t0_block, const DropInfo& drop) {
+                                            int t0_wave, int span, float* kshare, int t0_block, const DropInfo& drop) {
   const int lane = threadIdx.x & (kWave - 1);
   const int n = it.n_tokens;
   const int c = a.c;
@@ -189,14 +195,6 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     ch[s] = active[s] ? (uint32_t)raw : 0u;
   }
 
-  // Row i's destination is computed by lane i, then handed to the whole wave as a scalar.
-  int32_t my_row = 0;
-  {
-    int t = t0 + (lane & (kDecRows - 1));
-    const int64_t hop = t >= drop.split ? drop.jump : 0;
-    if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
-  }
-
   const uint8_t* kmeta = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
   const uint8_t* kcodes = kmeta + geo.kmeta;
   const uint8_t* vmeta = kcodes + geo.codes;
@@ -205,50 +203,62 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   const uint8_t* codes = is_v ? vcodes : kcodes;
   const int heads = c / kGroup;
 
-  // metadata: K = the two channels of the span this thread prepares for the whole block;
-  // V = group (row lane / H, head lane % H) of this unit
+  // what one unit loads: the destination row of row i (computed by lane i), the V metadata word of group
+  // (row lane / H, head lane % H), and the code words
+  int32_t my_row = 0;
   uint32_t vm = 0;
   bool v_owner = false;
+  Codes<BITS> cw[kDecRows][kDecSegs];
+  auto load_unit = [&](int t0) {
+    {
+      int t = t0 + (lane & (kDecRows - 1));
+      const int64_t hop = t >= drop.split ? drop.jump : 0;
+      my_row = 0;
+      if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
+    }
+    if (is_v) {
+      int t = t0 + lane / kDecHeads;
+      int head = span * kDecHeads + lane % kDecHeads;
+      v_owner = t < n && head < heads;
+      vm = 0;
+      if (v_owner) vm = gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < kDecRows; ++i) {
+      int t = t0 + i;
+      t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
+#pragma unroll
+      for (int s = 0; s < kDecSegs; ++s) cw[i][s].load(codes + (size_t)t * geo.row_bytes + ch[s] * BITS / 8);
+    }
+  };
+
+  // K metadata: the channels of the span this thread prepares for the whole block
   uint32_t kwords[kDecPrep] = {};
   const int pc = span * kDecSpanCh + (int)threadIdx.x * kDecPrep;
   const bool pact = !is_v && pc < c;  // c is a multiple of 128, so the thread's channels are all inside or all outside
-  if (!is_v) {
-    if (pact) {
-      const uint8_t* mp = kmeta + ((size_t)(t0_block / kGroup) * c + pc) * 4;
-      if constexpr (kDecPrep == 2) {
-        const uintx2 m = gload<uintx2>(mp);
-        kwords[0] = m.x; kwords[1] = m.y;
-      } else {
-        const uintx4 m = gload<uintx4>(mp);
-        kwords[0] = m.x; kwords[1] = m.y; kwords[2] = m.z; kwords[3] = m.w;
-      }
+  if (pact) {
+    const uint8_t* mp = kmeta + ((size_t)(t0_block / kGroup) * c + pc) * 4;
+    if constexpr (kDecPrep == 1) {
+      kwords[0] = gload<uint32_t>(mp);
+    } else if constexpr (kDecPrep == 2) {
+      const uintx2 m = gload<uintx2>(mp);
+      kwords[0] = m.x; kwords[1] = m.y;
+    } else {
+      const uintx4 m = gload<uintx4>(mp);
+      kwords[0] = m.x; kwords[1] = m.y; kwords[2] = m.z; kwords[3] = m.w;
     }
-  } else {
-    int t = t0 + lane / kDecHeads;
-    int head = span * kDecHeads + lane % kDecHeads;
-    v_owner = t < n && head < heads;
-    if (v_owner) vm = gload<uint32_t>(vmeta + ((size_t)t * heads + head) * 4);
   }
-  Codes<BITS> cw[kDecRows][kDecSegs];
-#pragma unroll
-  for (int i = 0; i < kDecRows; ++i) {
-    int t = t0 + i;
-    t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
-#pragma unroll
-    for (int s = 0; s < kDecSegs; ++s) cw[i][s].load(codes + (size_t)t * geo.row_bytes + ch[s] * BITS / 8);
-  }
+  load_unit(t0_wave);
 
   if (!header_matches(hdr, DT, BITS, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes(), drop.orig_tokens,
                       drop.sink, drop.window)) {
     if (a.status != nullptr && lane == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
     return;
   }
-  int32_t rows[kDecRows];
-#pragma unroll
-  for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
 
-  // the row loop, instantiated with and without the explicit top-code rule
-  auto run = [&](auto fix_tag, auto&& param_of) {
+  // the row loop of one unit, instantiated with and without the explicit top-code rule
+  int32_t rows[kDecRows];
+  auto run = [&](int t0, auto fix_tag, auto&& param_of) {
     constexpr bool FIX = decltype(fix_tag)::value;
 #pragma unroll
     for (int i = 0; i < kDecRows; ++i) {
@@ -266,7 +276,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   using No = std::integral_constant<bool, false>;
 
   if (!is_v) {
-    // Every thread of the block prepares two channels of the span; the three arrays (minimum, scale,
+    // Every thread of the block prepares its channels of the span; the three arrays (minimum, scale,
     // top code) meet in LDS and every wave then picks up the 16 channels its lanes own.  All waves of
     // a K block reach the barrier, also those whose rows lie past the end of the blob.
     GroupParams gp[kDecSegs][kLaneCh];
@@ -283,7 +293,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
       }
     }
     const bool any_fix = __syncthreads_or(fix);
-    if (t0 >= n) return;  // wave-uniform, after the barrier
+    if (t0_wave >= n) return;  // wave-uniform, after the barrier
 #pragma unroll
     for (int s = 0; s < kDecSegs; ++s) {
       const int base = s * kStripCh + lane * kLaneCh;
@@ -295,32 +305,123 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
       }
     }
     auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
-    if (any_fix) run(Yes{}, param_of); else run(No{}, param_of);
-  } else {
-    if (t0 >= n) return;  // wave-uniform; V waves never meet at a barrier
-    GroupParams mine = {0.0f, 0.0f, 0u};
-    bool fix = false;
-    if (v_owner) {
-      mine = decode_params<DT, BITS>(vm);
-      fix = top_needs_fix<DT, BITS>(mine);
-    }
-    const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
-    // every (row, segment) pulls its group's three values from the lane that prepared them
-    auto param_of = [&](int i, int s) {
-      int src = i * kDecHeads + s * (kStripCh / kGroup) + (lane >> 4);
-      GroupParams p;
-      p.mn = __shfl(mine.mn, src);
-      p.scale = __shfl(mine.scale, src);
-      p.top = __shfl(mine.top, src);
-      return [p](int) -> const GroupParams& { return p; };
+    auto unit = [&](int u) {
+      const int t0 = t0_wave + u * kDecRows;
+      if (u > 0) {
+        if (t0 >= n) return;  // wave-uniform
+        load_unit(t0);
+      }
+#pragma unroll
+      for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
+      if (any_fix) run(t0, Yes{}, param_of); else run(t0, No{}, param_of);
     };
-    if (any_fix) run(Yes{}, param_of); else run(No{}, param_of);
+    unit(0);
+    if constexpr (kDecSub > 1) unit(1);
+    if constexpr (kDecSub > 2) unit(2);
+    if constexpr (kDecSub > 3) unit(3);
+  } else {
+    if (t0_wave >= n) return;  // wave-uniform; V waves never meet at a barrier
+    auto unit = [&](int u) {
+      const int t0 = t0_wave + u * kDecRows;
+      if (u > 0) {
+        if (t0 >= n) return;  // wave-uniform
+        load_unit(t0);
+      }
+#pragma unroll
+      for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
+      GroupParams mine = {0.0f, 0.0f, 0u};
+      bool fix = false;
+      if (v_owner) {
+        mine = decode_params<DT, BITS>(vm);
+        fix = top_needs_fix<DT, BITS>(mine);
+      }
+      const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+      // every (row, segment) pulls its group's three values from the lane that prepared them
+      auto param_of = [&](int i, int s) {
+        int src = i * kDecHeads + s * (kStripCh / kGroup) + (lane >> 4);
+        GroupParams p;
+        p.mn = __shfl(mine.mn, src);
+        p.scale = __shfl(mine.scale, src);
+        p.top = __shfl(mine.top, src);
+        return [p](int) -> const GroupParams& { return p; };
+      };
+      if (any_fix) run(t0, Yes{}, param_of); else run(t0, No{}, param_of);
+    };
+    unit(0);
+    if constexpr (kDecSub > 1) unit(1);
+    if constexpr (kDecSub > 2) unit(2);
+    if constexpr (kDecSub > 3) unit(3);
+  }
+}
+
+// Raw level: a unit copies its rows from the blob (K rows, then V rows, per layer) to their destination rows.
+template <int DT>
+__device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh_item& it, int item_idx, int lam, bool is_v,
+                                                int t0_wave, int span, const DropInfo& drop) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int n = it.n_tokens;
+  const int c = a.c;
+  const uint8_t* blob = static_cast<const uint8_t*>(it.blob);
+  const LayerGeom geo = layer_geom(n, c, 16);
+  const HeaderWords hdr = load_header(blob);
+  bool active[kDecSegs];
+  uint32_t ch[kDecSegs];
+#pragma unroll
+  for (int s = 0; s < kDecSegs; ++s) {
+    int raw = span * kDecSpanCh + s * kStripCh + lane * kLaneCh;
+    active[s] = raw < c;
+    ch[s] = active[s] ? (uint32_t)raw : 0u;
+  }
+  const uint8_t* rows_in = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes() + (is_v ? geo.codes : 0);
+  uint16_t* dst = (is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride;
+  const bool ok = header_matches(hdr, DT, 16, a.l, n, c, kHeaderBytes + (size_t)a.l * geo.layer_bytes(), drop.orig_tokens,
+                                 drop.sink, drop.window);
+  if (!ok) {
+    if (a.status != nullptr && lane == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
+    return;
+  }
+#pragma unroll
+  for (int u = 0; u < kDecSub; ++u) {
+    const int t0 = t0_wave + u * kDecRows;
+    if (t0 >= n) return;  // wave-uniform
+    int32_t my_row = 0;
+    {
+      int t = t0 + (lane & (kDecRows - 1));
+      const int64_t hop = t >= drop.split ? drop.jump : 0;
+      if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
+    }
+    uintx4 d[kDecRows][kDecSegs];
+#pragma unroll
+    for (int i = 0; i < kDecRows; ++i) {
+      int t = t0 + i;
+      t = t < n ? t : n - 1;  // rows past the end re-read the last row and are not stored
+#pragma unroll
+      for (int s = 0; s < kDecSegs; ++s) d[i][s] = gload_stream<uintx4>(rows_in + (size_t)t * geo.row_bytes + ch[s] * 2u);
+    }
+#pragma unroll
+    for (int i = 0; i < kDecRows; ++i) {
+      const int32_t r = __builtin_amdgcn_readlane(my_row, i);
+      if (t0 + i < n) {  // wave-uniform
+        uint16_t* row = dst + (int64_t)r * a.token_stride;
+#pragma unroll
+        for (int s = 0; s < kDecSegs; ++s)
+          if (active[s]) gstore16(row + ch[s], make_uint4(d[i][s].x, d[i][s].y, d[i][s].z, d[i][s].w));
+      }
+    }
   }
 }
 
 // grid = (64-row blocks x spans, 2 * l, items); span fastest; wave w of a block takes rows 8 w .. 8 w + 7 of its 64.
+#ifndef KVH_DEC_WPE
+#define KVH_DEC_WPE 0  // waves per SIMD the register allocation is held to (0 = compiler's choice)
+#endif
+#if KVH_DEC_WPE
+#define KVH_DEC_OCC __attribute__((amdgpu_waves_per_eu(KVH_DEC_WPE, KVH_DEC_WPE)))
+#else
+#define KVH_DEC_OCC
+#endif
 template <int DT>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
+__global__ __launch_bounds__(kDecThreads) KVH_DEC_OCC void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
 #ifndef KVH_DEC_MAP
 #define KVH_DEC_MAP 1
@@ -400,8 +501,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
   const int strip = bx % nspans;
-  const int t0_block = (bx / nspans) * (kDecWaves * kDecRows);
-  const int t0 = t0_block + wave * kDecRows;
+  const int t0_block = (bx / nspans) * kDecBlockRows;
+  const int t0 = t0_block + wave * (kDecRows * kDecSub);
   if (it.n_tokens < 1 || t0_block >= it.n_tokens) return;  // block-uniform
   const int lam = lay_kv >> 1;
   const bool is_v = lay_kv & 1;
@@ -409,6 +510,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
     case 0: decode_unit<DT, 8>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
     case 1: decode_unit<DT, 4>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
     case 2: decode_unit<DT, 2>(a, it, item_idx, lam, is_v, t0, strip, kshare, t0_block, drop); break;
+    case kRawLevel: decode_raw_unit<DT>(a, it, item_idx, lam, is_v, t0, strip, drop); break;
     default:
       if (a.status != nullptr && (threadIdx.x & (kWave - 1)) == 0) a.status[item_idx] = KVH_DEV_HEADER_MISMATCH;
       break;
@@ -417,7 +519,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DecodeParams a) {
 
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream) {
   const int nspans = (a.c + kDecSpanCh - 1) / kDecSpanCh;
-  const unsigned gx = (unsigned)(((max_tokens + kDecRows * kDecWaves - 1) / (kDecRows * kDecWaves)) * nspans);
+  const unsigned gx = (unsigned)(((max_tokens + kDecBlockRows - 1) / kDecBlockRows) * nspans);
   dim3 grid(gx, (unsigned)(2 * a.l), (unsigned)n_items);
   DecodeParams b = a;
   b.max_tokens = max_tokens;

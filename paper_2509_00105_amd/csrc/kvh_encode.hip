@@ -230,6 +230,35 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
   }
 }
 
+// Raw level: the rows of the block's tile and strip go into the blob as they are (K rows, then V rows, per layer).
+template <int DT>
+__device__ __forceinline__ void encode_raw_block(const EncodeParams& a, const kvh_enc_item& it, uint8_t* layer_base,
+                                                 const LayerGeom& geo, int lam, bool is_v, int tile, int strip, int split,
+                                                 int64_t jump) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = it.n_tokens;
+  const int ch_raw = strip * kStripCh + lane * kLaneCh;
+  const bool active = ch_raw < a.c;
+  const int ch0 = active ? ch_raw : 0;
+  const int t_first = tile * kEncTile + wave * kEncRows;
+  if (t_first >= n) return;  // wave-uniform
+  const uint8_t* src = reinterpret_cast<const uint8_t*>((is_v ? a.v : a.k) + (int64_t)lam * a.layer_stride);
+  uint8_t* rows = layer_base + (is_v ? geo.codes : 0);  // kmeta and vmeta are empty at this level
+  uintx4 d[kEncRows];
+#pragma unroll
+  for (int i = 0; i < kEncRows; ++i) {
+    int t = t_first + i;
+    t = t < n ? t : n - 1;
+    d[i] = gload_rows<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + (uint32_t)ch0 * 2u);
+  }
+#pragma unroll
+  for (int i = 0; i < kEncRows; ++i) {
+    const int t = t_first + i;
+    if (t < n && active) gstore_codes<uintx4>(uniform(rows + (size_t)t * geo.row_bytes) + (uint32_t)ch0 * 2u, d[i]);
+  }
+}
+
 // all-reduce over the 16 lanes of a DPP row (= one head): rotate by 8, 4, 2, 1 and combine
 template <bool IS_MIN>
 __device__ __forceinline__ float row16_reduce(float v) {
@@ -405,6 +434,10 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
     gstore<uint32_t>(blob + 4 * threadIdx.x, w);
   }
   uint8_t* layer_base = blob + kHeaderBytes + (size_t)lam * geo.layer_bytes();
+  if (bits == 16) {
+    encode_raw_block<DT>(a, it, layer_base, geo, lam, is_v, tile, strip, split, jump);
+    return;
+  }
   if (!is_v) {
     switch (bits) {
       case 8: encode_k_block<DT, 8>(a, it, layer_base, geo, lam, tile, strip, red, split, jump); break;

@@ -608,7 +608,8 @@ __global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(Transc
   const int lam = blockIdx.y >> 1;
   const bool is_v = blockIdx.y & 1;
   const int bi = level_bits(it.level_in), bo = level_bits(it.level_out);
-  if (bi < 0 || bo < 0 || it.n_tokens > a.max_tokens) {  // also: more tokens than the grid covers
+  // refused: a level out of range, the raw level (no codes to transcode), more tokens than the grid covers
+  if (bi < 0 || bo < 0 || bi > 8 || bo > 8 || it.n_tokens > a.max_tokens) {
     if (a.status != nullptr && threadIdx.x == 0) a.status[blockIdx.z] = KVH_DEV_HEADER_MISMATCH;
     return;
   }

@@ -77,7 +77,7 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert enc(None, 0, 1, 128, 1024, 0, P, big, None) == E_ARG
     assert enc(v, 0, 1, 128, 1024, 0, None, big, None) == E_ARG
     assert enc(v, 2, 1, 128, 1024, 0, P, big, None) == E_ARG
-    assert enc(v, 0, 1, 128, 1024, 3, P, big, None) == E_LEVEL
+    assert enc(v, 0, 1, 128, 1024, 4, P, big, None) == E_LEVEL
     assert enc(v, 0, 1, 128, 1024, -1, P, big, None) == E_LEVEL
     assert enc(v, 0, 0, 128, 1024, 0, P, big, None) == E_SHAPE
     assert enc(v, 0, 1, 0, 1024, 0, P, big, None) == E_SHAPE
@@ -142,6 +142,7 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert tc(P, 5, 1, 128, 1024, 0, 2, Q, big, None, None) == E_ARG
     assert tc(P, 0, 1, 128, 1024, 3, 2, Q, big, None, None) == E_LEVEL
     assert tc(P, 0, 1, 128, 1024, 0, -1, Q, big, None, None) == E_LEVEL
+    assert tc(P, 0, 1, 128, 1024, 0, 3, Q, big, None, None) == E_LEVEL      # the raw level holds rows, not codes
     assert tc(P, 0, 1, 128, 1000, 0, 2, Q, big, None, None) == E_SHAPE
     assert tc(P, 0, 1, 128, 1024, 0, 2, Q, lib.kvh_blob_size(1, 128, 1024, 2) - 1, None, None) == E_SIZE
     assert tc(P + 8, 0, 1, 128, 1024, 0, 2, Q, big, None, None) == E_ALIGN

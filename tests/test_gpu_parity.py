@@ -241,7 +241,7 @@ def test_chunked_and_batched_encode_match_per_chunk_oracle(kvh):
             assert_same_bits(to_host(tv[:, base + i * chunk:base + i * chunk + n]), wv, dt, "%s V chunk %d" % (what, i))
     assert not sk[:, :base].any() and not sk[:, base + N:].any()
     with pytest.raises(kvh.KVHError):
-        kvh.decode_chunked(blobs2, offs, [2, 0, 1, 3], chunk, N, sk, sv)       # a level out of range: nothing launched
+        kvh.decode_chunked(blobs2, offs, [2, 0, 1, 4], chunk, N, sk, sv)       # a level out of range: nothing launched
     with pytest.raises(kvh.KVHError):
         kvh.decode_chunked(blobs2, offs[:3], levels[:3], 320, N, sk, sv)        # chunk not a multiple of 128
 

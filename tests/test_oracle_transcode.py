@@ -172,7 +172,7 @@ def test_error_paths():
     assert oracle.transcode_rc(b, dt, l, n, c, 0, 2, out[: 16]) == oracle.E_SIZE
     assert oracle.transcode_rc(b, dt, l, n, c, 1, 2, out[:-1]) == oracle.E_SIZE
     assert oracle.transcode_rc(b[:-1], dt, l, n, c, 1, 2, out) == oracle.E_SIZE
-    assert oracle.transcode_rc(b, dt, l, n, c, 1, 3, out) == oracle.E_LEVEL
+    assert oracle.transcode_rc(b, dt, l, n, c, 1, 4, out) == oracle.E_LEVEL
     assert oracle.transcode_rc(b, dt, l, n, c, -1, 2, out) == oracle.E_LEVEL
     assert oracle.transcode_rc(b, dt, l, n, 100, 1, 2, out) == oracle.E_SHAPE
     assert oracle.transcode_rc(b, BF16, l, n, c, 1, 2, out) == oracle.E_HEADER
