@@ -422,6 +422,24 @@ def main():
                 streamed.append({"bits": kvh.level_bits(level), "launches": n_chunks,
                                  "decode_streamed": rate_fields(d, u_, b_), "encode_streamed": rate_fields(e, u_, b_)})
 
+    # Outside the timed region: the raw level (an entry stored in full quality: rows copied into and out of the blob),
+    # one batched launch over the 32 chunks in each direction.
+    raw_level = []
+    if not args.no_extras:
+        with torch.cuda.stream(stream):
+            rsize = kvh.blob_size(l, chunk, c, 3)
+            rblobs = torch.empty(n_chunks * rsize, dtype=torch.uint8, device=dev)
+            rptrs = [rblobs.data_ptr() + i * rsize for i in range(n_chunks)]
+            rei = kvh.make_enc_items(rptrs, [i * chunk for i in range(n_chunks)], [chunk] * n_chunks, [3] * n_chunks, dev)
+            rdi = kvh.make_dec_items(rptrs, [chunk] * n_chunks, [3] * n_chunks, [i * chunk for i in range(n_chunks)], [0] * n_chunks, dev)
+            status[0].zero_()
+            e = time_reps(torch, stream, lambda: kvh.encode_batch(rei, n_chunks, chunk, kv[0], kv[1], stream=stream), 5)
+            d = time_reps(torch, stream, lambda: kvh.decode_batch(rdi, n_chunks, chunk, out[0], out[1], status=status[0], stream=stream), 5)
+            assert int(status[0].abs().sum().item()) == 0 and torch.equal(out, kv)
+            raw_level = [dict(rate_fields(e, 2 * l * N * c * 2, rblobs.numel()), op="encode", bits=16),
+                         dict(rate_fields(d, 2 * l * N * c * 2, rblobs.numel()), op="decode", bits=16)]
+            del rblobs
+
     # Also outside the timed region: the token-dropping method on the whole tensor as ONE entry of N tokens,
     # keeping sink = 128 and window = N/2 - 128 tokens (rate 1/2), stored at 8 and at 2 bits.
     dropping = []
@@ -570,7 +588,7 @@ def main():
     freqs = 1.0 / (1.0 + prng.permutation(n_entries)) ** 0.8
     sens = np.clip(prng.lognormal(0.0, 0.75, n_entries), 0.0, 3.5)
     loss = {16: 0.0, 8: 0.002, 4: 0.03, 2: 0.25}
-    per_chunk = [2 * l * chunk * c * 2] + [kvh.blob_size(l, chunk, c, lv) for lv in range(3)]
+    per_chunk = [kvh.blob_size(l, chunk, c, 3)] + [kvh.blob_size(l, chunk, c, lv) for lv in range(3)]  # raw level first
     sizes_p = [[float(pc * (n // chunk)) for pc in per_chunk] for n in lengths]
     quals_p = [[1.0 - s_ * loss[b] for b in (16, 8, 4, 2)] for s_ in sens]
     tiers_p = [(load_path[0]["pcie_GBps"] * 1e9, 100e9), (1e9, 400e9)]
@@ -655,6 +673,7 @@ def main():
         "copy_probe_GBps": copy_gbps,
         "memory_probes": probes,
         "streamed_chunk_by_chunk": streamed,
+        "raw_level": raw_level,
         "other_workloads": others,
         "token_dropping": dropping,
         "transcode": transcode,

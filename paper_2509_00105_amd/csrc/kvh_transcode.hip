@@ -317,6 +317,89 @@ __device__ __forceinline__ void lookup_row(uint8_t* out, const InCodes<BI>& cw, 
   }
 }
 
+// ---- 8 -> 2 bits: the code -> code map of a group as a polynomial of the input code ------------------
+// The map f(q) of a group (reconstruct, round to the 16-bit type, re-position, round to a code) is a monotone step
+// function of q with three steps, because every operation in it is monotone.  If some cheap monotone function
+// g(q) is shown to round to f(q) at the last code before each step and at the first code of each step (and at both
+// ends), the two agree at all 256 codes, and an element costs  byte -> float, g, float -> code  instead of the seven
+// floating-point instructions of the definition.  Two forms of g are used:
+//   standard  g(q) = q / 85: steps at 43, 128, 213, which is where the steps of a group lie unless the rounding to
+//             the 16-bit type moves them (it does when the group sits far from zero compared with its range);
+//             recognised by evaluating f at the six codes around those steps;
+//   fitted    the parabola through the three step positions of the group, found by bisection with f itself, and
+//             accepted only if evaluating it with the very instructions of the row loop reproduces f at the codes
+//             around its steps and at both ends, with a slope that keeps it monotone.
+// A group that passes neither test (a range of a few units in the last place, say) sends its block, or its batch
+// of V rows, down the arithmetic route above.  Bit-exactness therefore never rests on the fit, only on the checks.
+struct Quad {
+  float a, b, c;  // g(q) = (a q + b) q + c
+};
+enum : uint32_t { kStandard = 0u, kFitted = 1u, kHard = 2u };
+
+// f(q) by the definition (the top code decodes to the stored maximum).
+template <int DT>
+__device__ __forceinline__ uint32_t code82(float q, const TcParams& p) {
+  const uint32_t pk = pack2<DT>(recon(q, p.scale, p.mn), 0.0f);
+  float x = t16_to_f32<DT>(pk & 0xffffu);
+  x = q == 255.0f ? p.top : x;
+  return __builtin_amdgcn_cvt_pk_u8_f32((x - p.mn) * p.inv, 0, 0u);
+}
+// g(q) exactly as the row loop evaluates it
+__device__ __forceinline__ float quad_value(float q, const Quad& g) { return __builtin_fmaf(__builtin_fmaf(g.a, q, g.b), q, g.c); }
+__device__ __forceinline__ uint32_t quad_code(float q, const Quad& g) { return __builtin_amdgcn_cvt_pk_u8_f32(quad_value(q, g), 0, 0u); }
+
+template <int DT>
+__device__ __forceinline__ uint32_t classify82(const TcParams& p, Quad& g) {
+  g = Quad{0.0f, 0.0f, 0.0f};
+  if (p.inv == 0.0f) return kFitted;  // degenerate group: every code becomes 0, and so does g
+  const bool standard = code82<DT>(42.0f, p) == 0u && code82<DT>(43.0f, p) == 1u && code82<DT>(127.0f, p) == 1u &&
+                        code82<DT>(128.0f, p) == 2u && code82<DT>(212.0f, p) == 2u && code82<DT>(213.0f, p) == 3u;
+  if (standard) {
+    g.b = 1.0f / 85.0f;  // what a standard group contributes where its neighbours need the fitted form
+    return kStandard;
+  }
+  // first code of each step: f(0) = 0 and f(255) = 3 bracket all three
+  float t[3];
+#pragma unroll
+  for (int k = 1; k <= 3; ++k) {
+    int lo = 0, hi = 255;
+#pragma unroll 1
+    for (int it = 0; it < 8; ++it) {
+      const int mid = (lo + hi) >> 1;
+      if (code82<DT>((float)mid, p) >= (uint32_t)k) hi = mid; else lo = mid;
+    }
+    t[k - 1] = (float)hi;
+  }
+  if (!(t[0] < t[1] && t[1] < t[2])) return kHard;
+  // parabola through (t_k - 1/2, k - 1/2)
+  const float x1 = t[0] - 0.5f, x2 = t[1] - 0.5f, x3 = t[2] - 0.5f;
+  const float d1 = 1.0f / (x2 - x1), d2 = 1.0f / (x3 - x2);
+  g.a = (d2 - d1) / (x3 - x1);
+  g.b = d1 - g.a * (x1 + x2);
+  g.c = 0.5f - (g.a * x1 + g.b) * x1;
+  bool ok = quad_code(0.0f, g) == 0u && quad_code(255.0f, g) == 3u;
+#pragma unroll
+  for (int k = 1; k <= 3; ++k) ok = ok && quad_code(t[k - 1] - 1.0f, g) == (uint32_t)(k - 1) && quad_code(t[k - 1], g) == (uint32_t)k;
+  // slope at both ends well above what rounding errors in g could undo
+  ok = ok && g.b >= 0x1p-9f && __builtin_fmaf(510.0f, g.a, g.b) >= 0x1p-9f;
+  return ok ? kFitted : kHard;
+}
+
+// One row of a lane through g.  coef(j) gives the polynomial of channel j (unused when STANDARD).
+template <bool STANDARD, typename C>
+__device__ __forceinline__ void poly_row82(uint8_t* out, const InCodes<8>& cw, C&& coef) {
+  constexpr float kStep = 1.0f / 85.0f;
+  float t[kTcLaneCh];
+  uint32_t e[4];
+  cw.spread(e);
+#pragma unroll
+  for (int j = 0; j < kTcLaneCh; ++j) {
+    const float q = cw.get(e, j);
+    if constexpr (STANDARD) t[j] = q * kStep; else t[j] = quad_value(q, coef(j));
+  }
+  store_codes16<2>(out, t);
+}
+
 struct HeaderWords {
   uintx4 a, b, c;
 };
@@ -337,7 +420,8 @@ __device__ __forceinline__ bool source_header_ok(const HeaderWords& h, int dt, i
 
 template <int DT, int BI, int BO>
 __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const kvh_tc_item& it, int item_idx, int lam,
-                                                bool is_v, int g, int span, TcParams* kpar) {
+                                                bool is_v, int g, int span, TcParams* kpar, float* kquad,
+                                                uint32_t* kflags) {
   using Yes = std::integral_constant<bool, true>;
   using No = std::integral_constant<bool, false>;
   const int lane = threadIdx.x & (kWave - 1);
@@ -458,19 +542,71 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
       return;
     }
     bool fix = false;
+    [[maybe_unused]] uint32_t worst = kStandard;  // 8 -> 2: the least tractable of this thread's channels
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       bool f;
       const TcParams p = tc_params<DT, BI, BO>(meta[e], om[e], f);
       fix |= pact && f;
       const int lc = (int)threadIdx.x * 2 + e;  // channel within the span; its user is lane lc / 16, slot lc % 16
-      kpar[(lc % kTcLaneCh) * kWave + lc / kTcLaneCh] = p;
+      const int slot = (lc % kTcLaneCh) * kWave + lc / kTcLaneCh;
+      kpar[slot] = p;
+      if constexpr (BI == 8 && BO == 2) {
+        Quad gq;
+        const uint32_t cls = classify82<DT>(p, gq);
+        if (pact && cls > worst) worst = cls;
+        kquad[slot] = gq.a;
+        kquad[kTcLaneCh * kWave + slot] = gq.b;
+        kquad[2 * kTcLaneCh * kWave + slot] = gq.c;
+      }
     }
     if (pact) {
       uintx2 o = {om[0], om[1]};
       gstore<uintx2>(out_layer + ((size_t)g * c + pc) * 4, o);
     }
-    const bool any_fix = __syncthreads_or(fix);
+    bool any_fix;
+    if constexpr (BI == 8 && BO == 2) {
+      // three block-wide verdicts through one barrier: every wave leaves its own in LDS
+      const uint32_t mine = (__builtin_amdgcn_ballot_w64(fix) != 0 ? 1u : 0u) |
+                            (__builtin_amdgcn_ballot_w64(worst != kStandard) != 0 ? 2u : 0u) |
+                            (__builtin_amdgcn_ballot_w64(worst == kHard) != 0 ? 4u : 0u);
+      if (lane == 0) kflags[wave] = mine;
+      __syncthreads();
+      uint32_t all = 0;
+#pragma unroll
+      for (int w = 0; w < kTcWaves; ++w) all |= kflags[w];
+      all = (uint32_t)__builtin_amdgcn_readfirstlane((int)all);
+      any_fix = (all & 1u) != 0;
+      if ((all & 4u) == 0) {  // no hard group in the block: the polynomial route
+        if (t_first >= n) return;  // wave-uniform, after the barrier
+        auto poly_rows = [&](auto standard_tag) {
+          constexpr bool STANDARD = decltype(standard_tag)::value;
+          Quad gq[kTcLaneCh];
+#pragma unroll
+          for (int j = 0; j < kTcLaneCh; ++j) {
+            gq[j].a = STANDARD ? 0.0f : kquad[j * kWave + lane];
+            gq[j].b = STANDARD ? 0.0f : kquad[(kTcLaneCh + j) * kWave + lane];
+            gq[j].c = STANDARD ? 0.0f : kquad[(2 * kTcLaneCh + j) * kWave + lane];
+          }
+#pragma unroll 1
+          for (int t0 = t_first;;) {
+#pragma unroll
+            for (int i = 0; i < kRowsK; ++i) {
+              if (t0 + i < n && active)
+                poly_row82<STANDARD>(out_codes + (size_t)(t0 + i) * go.row_bytes, cw[i], [&gq](int j) -> const Quad& { return gq[j]; });
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            t0 += kRowsK;
+            if (t0 >= t_first + kTcRows || t0 >= n) break;
+            load_batch(t0, RowsK{});
+          }
+        };
+        if ((all & 2u) == 0) poly_rows(Yes{}); else poly_rows(No{});
+        return;
+      }
+    } else {
+      any_fix = __syncthreads_or(fix);
+    }
     if (t_first >= n) return;  // wave-uniform, after the barrier
     // The common path never touches `top`; reading it only where the rule is needed keeps that path's
     // register count down.
@@ -550,6 +686,30 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
             gstore<uint32_t>(out_vmeta + off, om);
           }
           const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
+          if constexpr (BI == 8 && BO == 2) {
+            Quad gq;
+            uint32_t cls = classify82<DT>(mine, gq);
+            if (!(t < n && head < heads)) cls = kStandard;  // a lane without a group has no say
+            if (__builtin_amdgcn_ballot_w64(cls == kHard) == 0) {
+              const bool all_standard = __builtin_amdgcn_ballot_w64(cls != kStandard) == 0;
+              constexpr int kFirst = decltype(first_tag)::value;
+#pragma unroll
+              for (int i = 0; i < kTcBatch; ++i) {
+                if (tb + i < n) {  // wave-uniform; the shuffles are taken with the whole wave enabled
+                  const int owner = i * kTcSpanHeads + lane / (kGroup / kTcLaneCh);
+                  uint8_t* out_row = out_codes + (size_t)(tb + i) * go.row_bytes;
+                  if (all_standard) {
+                    if (active) poly_row82<true>(out_row, cw[kFirst + i], [&gq](int) -> const Quad& { return gq; });
+                  } else {
+                    const Quad gr = {__shfl(gq.a, owner), __shfl(gq.b, owner), __shfl(gq.c, owner)};
+                    if (active) poly_row82<false>(out_row, cw[kFirst + i], [&gr](int) -> const Quad& { return gr; });
+                  }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+              }
+              return;
+            }
+          }
           auto param_of = [&](int i) {
             const int owner = i * kTcSpanHeads + lane / (kGroup / kTcLaneCh);
             TcParams p;
@@ -583,6 +743,8 @@ __device__ __forceinline__ void transcode_block(const TranscodeParams& a, const 
 template <int DT>
 __global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(TranscodeParams a) {
   __shared__ TcParams kpar[kTcLaneCh * kWave];  // 16 KiB, [slot][lane]
+  __shared__ float kquad[3 * kTcLaneCh * kWave];  // 12 KiB, [coefficient][slot][lane]: the 8 -> 2 polynomials
+  __shared__ uint32_t kflags[kTcWaves];
   kvh_tc_item it;
   if (a.items != nullptr) {
     const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + blockIdx.z);
@@ -614,7 +776,7 @@ __global__ __launch_bounds__(kTcThreads) KVH_TC_OCC void transcode_kernel(Transc
     return;
   }
 #define KVH_TC_CASE(BI, BO) \
-  case BI * 16 + BO: transcode_block<DT, BI, BO>(a, it, blockIdx.z, lam, is_v, g, span, kpar); break;
+  case BI * 16 + BO: transcode_block<DT, BI, BO>(a, it, blockIdx.z, lam, is_v, g, span, kpar, kquad, kflags); break;
   switch (bi * 16 + bo) {
     KVH_TC_CASE(8, 8) KVH_TC_CASE(8, 4) KVH_TC_CASE(8, 2)
     KVH_TC_CASE(4, 8) KVH_TC_CASE(4, 4) KVH_TC_CASE(4, 2)
