@@ -200,3 +200,43 @@ def test_transcode_argument_errors(kvh):
     with pytest.raises(ValueError):
         kvh.transcode(src.cpu(), dt, l, n, c, 0, 2)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("mix", ["offset", "offset+constant", "offset+tiny"])
+def test_transcode_8_to_2_away_from_zero(kvh, mix, dt):
+    """Groups that sit far from zero compared with their range: the rounding to the 16-bit type then moves the steps
+    of the 8 -> 2 code map off 43 / 128 / 213 (for bf16 in a good share of the groups), which is the case the fitted
+    form of the map exists for; constant channels add degenerate groups to such blocks, and channels whose range is
+    a few units in the last place add groups that no polynomial is accepted for.  All must equal the oracle."""
+    l, n, c = 2, 300, 1024
+    rng = np.random.default_rng(77 + dt)
+    sig = np.exp(rng.standard_normal((l, 1, c))).astype(np.float32)
+    koff = (rng.standard_normal((l, 1, c)) * 5).astype(np.float32) * sig          # K: an offset per channel
+    voff = (rng.standard_normal((l, n, 1)) * 5).astype(np.float32)                 # V: an offset per token
+    kf = rng.standard_normal((l, n, c)).astype(np.float32) * sig + koff
+    vf = rng.standard_normal((l, n, c)).astype(np.float32) + voff
+    if mix == "offset+constant":
+        kf[:, :, 5::64] = 3.25
+        vf[:, 7::50, 128:256] = -1.5
+    if mix == "offset+tiny":
+        kf[:, :, 9::97] = 100.0 + (rng.integers(0, 3, (l, n, kf[:, :, 9::97].shape[2])) * (0.5 if dt == BF16 else 0.0625)).astype(np.float32)
+    k, v = gen._cast_to_bits(kf, dt), gen._cast_to_bits(vf, dt)
+    src = oracle.encode(k, v, dt, 0)
+    # the premise of the test, checked with the oracle: some K groups visibly have steps off the standard places (an
+    # element must sit right at a moved step for that to show, so far more groups have moved steps than show it)
+    if dt == BF16:
+        wk, _ = oracle.decode(src, dt, l, n, c, 0)
+        two = oracle.encode(wk, wk, dt, 2)
+        off0 = oracle.section_offsets(l, n, c, 0, 0); off2 = oracle.section_offsets(l, n, c, 2, 0)
+        q8 = src[off0["kcodes"]:off0["kcodes"] + 128 * c].reshape(128, c).astype(np.int64)
+        raw2 = two[off2["kcodes"]:off2["kcodes"] + 128 * c // 4].reshape(128, c // 4)
+        q2 = np.stack([(raw2 >> (2 * i)) & 3 for i in range(4)], axis=2).reshape(128, c)
+        moved = ((q8 + 42) * 772 >> 16) != q2        # the standard map: steps at 43, 128, 213
+        assert moved.any(axis=0).mean() > 0.005
+    want = oracle.transcode(src, dt, l, n, c, 0, 2)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, 0, 2, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    assert_same_blob(got.cpu().numpy(), want, "8 -> 2, %s" % mix)
