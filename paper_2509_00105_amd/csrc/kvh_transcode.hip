@@ -326,7 +326,7 @@ __device__ __forceinline__ void lookup_row(uint8_t* out, const InCodes<BI>& cw, 
 //   standard  g(q) = q / 85: steps at 43, 128, 213, which is where the steps of a group lie unless the rounding to
 //             the 16-bit type moves them (it does when the group sits far from zero compared with its range);
 //             recognised by evaluating f at the six codes around those steps;
-//   fitted    the parabola through the three step positions of the group, found by bisection with f itself, and
+//   fitted    the parabola through the three step positions of the group, found by evaluating f itself, and
 //             accepted only if evaluating it with the very instructions of the row loop reproduces f at the codes
 //             around its steps and at both ends, with a slope that keeps it monotone.
 // A group that passes neither test (a range of a few units in the last place, say) sends its block, or its batch
@@ -358,23 +358,38 @@ __device__ __forceinline__ uint32_t classify82(const TcParams& p, Quad& g) {
     g.b = 1.0f / 85.0f;  // what a standard group contributes where its neighbours need the fitted form
     return kStandard;
   }
-  // first code of each step: f(0) = 0 and f(255) = 3 bracket all three
+  // First code of each step.  The steps lie within a few codes of 43, 128, 213, so each is looked for from there,
+  // one code at a time in the direction the two evaluations at the usual place point to; a step further away than
+  // kReach codes makes the group a hard one.
+  constexpr int kReach = 6;
   float t[3];
+  bool found = true;
 #pragma unroll
   for (int k = 1; k <= 3; ++k) {
-    int lo = 0, hi = 255;
+    const float hi0 = k == 1 ? 43.0f : k == 2 ? 128.0f : 213.0f;
+    const bool below = code82<DT>(hi0 - 1.0f, p) >= (uint32_t)k;  // the step is at or before the code below the usual place
+    const bool above = code82<DT>(hi0, p) < (uint32_t)k;          // the step is after the usual place
+    float tk = hi0;
+    bool searching = below || above;
+    const float dir = below ? -1.0f : 1.0f;
+    float q = below ? hi0 - 1.0f : hi0;
 #pragma unroll 1
-    for (int it = 0; it < 8; ++it) {
-      const int mid = (lo + hi) >> 1;
-      if (code82<DT>((float)mid, p) >= (uint32_t)k) hi = mid; else lo = mid;
+    for (int step = 0; step < kReach && __builtin_amdgcn_ballot_w64(searching) != 0; ++step) {
+      q += dir;
+      const bool ge = code82<DT>(q, p) >= (uint32_t)k;
+      if (searching && ge != below) {  // crossed the step: going up, q is its first code; going down, q + 1 is
+        tk = below ? q + 1.0f : q;
+        searching = false;
+      }
     }
-    t[k - 1] = (float)hi;
+    found = found && !searching;
+    t[k - 1] = tk;
   }
-  if (!(t[0] < t[1] && t[1] < t[2])) return kHard;
-  // parabola through (t_k - 1/2, k - 1/2)
+  if (!found || !(t[0] >= 1.0f && t[0] < t[1] && t[1] < t[2] && t[2] <= 255.0f)) return kHard;
+  // parabola through (t_k - 1/2, k - 1/2); approximate reciprocals will do, the checks below are what counts
   const float x1 = t[0] - 0.5f, x2 = t[1] - 0.5f, x3 = t[2] - 0.5f;
-  const float d1 = 1.0f / (x2 - x1), d2 = 1.0f / (x3 - x2);
-  g.a = (d2 - d1) / (x3 - x1);
+  const float d1 = __builtin_amdgcn_rcpf(x2 - x1), d2 = __builtin_amdgcn_rcpf(x3 - x2);
+  g.a = (d2 - d1) * __builtin_amdgcn_rcpf(x3 - x1);
   g.b = d1 - g.a * (x1 + x2);
   g.c = 0.5f - (g.a * x1 + g.b) * x1;
   bool ok = quad_code(0.0f, g) == 0u && quad_code(255.0f, g) == 3u;
