@@ -294,31 +294,37 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     }
     const bool any_fix = __syncthreads_or(fix);
     if (t0_wave >= n) return;  // wave-uniform, after the barrier
+    // The common path never touches `top`; reading it only where the rule is needed keeps that path's register
+    // count down.
+    auto k_units = [&](auto fix_tag) {
+      constexpr bool FIX = decltype(fix_tag)::value;
 #pragma unroll
-    for (int s = 0; s < kDecSegs; ++s) {
-      const int base = s * kStripCh + lane * kLaneCh;
+      for (int s = 0; s < kDecSegs; ++s) {
+        const int base = s * kStripCh + lane * kLaneCh;
 #pragma unroll
-      for (int j = 0; j < kLaneCh; ++j) {
-        gp[s][j].mn = kshare[base + j];
-        gp[s][j].scale = kshare[kDecSpanCh + base + j];
-        gp[s][j].top = __builtin_bit_cast(uint32_t, kshare[2 * kDecSpanCh + base + j]);
+        for (int j = 0; j < kLaneCh; ++j) {
+          gp[s][j].mn = kshare[base + j];
+          gp[s][j].scale = kshare[kDecSpanCh + base + j];
+          gp[s][j].top = FIX ? __builtin_bit_cast(uint32_t, kshare[2 * kDecSpanCh + base + j]) : 0u;
+        }
       }
-    }
-    auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
-    auto unit = [&](int u) {
-      const int t0 = t0_wave + u * kDecRows;
-      if (u > 0) {
-        if (t0 >= n) return;  // wave-uniform
-        load_unit(t0);
-      }
+      auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
+      auto unit = [&](int u) {
+        const int t0 = t0_wave + u * kDecRows;
+        if (u > 0) {
+          if (t0 >= n) return;  // wave-uniform
+          load_unit(t0);
+        }
 #pragma unroll
-      for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
-      if (any_fix) run(t0, Yes{}, param_of); else run(t0, No{}, param_of);
+        for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
+        run(t0, fix_tag, param_of);
+      };
+      unit(0);
+      if constexpr (kDecSub > 1) unit(1);
+      if constexpr (kDecSub > 2) unit(2);
+      if constexpr (kDecSub > 3) unit(3);
     };
-    unit(0);
-    if constexpr (kDecSub > 1) unit(1);
-    if constexpr (kDecSub > 2) unit(2);
-    if constexpr (kDecSub > 3) unit(3);
+    if (any_fix) k_units(Yes{}); else k_units(No{});
   } else {
     if (t0_wave >= n) return;  // wave-uniform; V waves never meet at a barrier
     auto unit = [&](int u) {
