@@ -377,6 +377,16 @@ int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* strea
 int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int reads_per_unit, int writes_per_unit,
                      void* stream);
 
+/* Self-test of the arithmetic shortcut behind the group parameters (Sec. 3.2's quantisation: scale = r / L and
+ * inv = L / r are correctly rounded fp32 quotients).  The kernels form both with a reciprocal and two fused
+ * corrections instead of the division sequence; that this returns the division's bits is a property of the
+ * device's reciprocal instruction, which this call checks on the device it runs on: every finite fp32 range r from
+ * 2^-100 (the smallest a non-degenerate group can have) upwards, about 1.9e9 values, at L = 255, 15, 3.  mismatches_dev: device array of 6 uint64 that the CALLER has zeroed (8-byte aligned); the kernel
+ * adds the number of values whose r / L differs at 8 / 4 / 2 bits to [0..2] and whose L / r differs to [3..5].
+ * All six are 0 on gfx950; anything else means the codec's parameters are not the specified ones on this device.
+ * About one second of GPU time.  Errors: KVH_E_ARG (null or misaligned pointer), KVH_E_HIP. */
+int kvh_selftest_division(uint64_t* mismatches_dev, void* stream);
+
 /* Static description of a status code. */
 const char* kvh_strerror(int status);
 

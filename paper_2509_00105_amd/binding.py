@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_stream_probe.restype = i32
         L.kvh_stream_probe.argtypes = [vp, vp, sz, i32, i32, vp]
+        L.kvh_selftest_division.restype = i32
+        L.kvh_selftest_division.argtypes = [vp, vp]
         L.kvh_decode_chunked.restype = i32
         L.kvh_decode_chunked.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_int8), i32, i32, i32, i32, i32,
                                          view, i64, vp, i32, vp, vp]
@@ -543,6 +545,14 @@ def stream_probe(dst: torch.Tensor, src: torch.Tensor, n_units: int, reads_per_u
         raise ValueError("buffers too small for this many units")
     _check(lib().kvh_stream_probe(dst.data_ptr(), src.data_ptr(), n_units, reads_per_unit, writes_per_unit,
                                   _stream_ptr(stream)), "kvh_stream_probe")
+
+
+def selftest_division(stream=None) -> list:
+    """kvh_selftest_division: mismatch counts [r/L at 8, 4, 2 bits, L/r at 8, 4, 2 bits] of the short quotient forms
+    against fp32 division over every possible group range; all zeros on a device the codec is exact on."""
+    out = torch.zeros(6, dtype=torch.int64, device="cuda")
+    _check(lib().kvh_selftest_division(out.data_ptr(), _stream_ptr(stream)), "kvh_selftest_division")
+    return out.cpu().tolist()
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -98,6 +98,46 @@ int launch_stream(void* dst, const void* src, size_t n_units, hipStream_t stream
 
 using namespace kvh;
 
+// ---- self-test of the short quotient forms ------------------------------------------------------
+// Every finite fp32 value from 2^-100 up (what the range of a non-degenerate group of finite values can be) goes
+// through range_over_levels and levels_over_range and through the divisions they stand for; out[0..2] count the
+// values where r / L differs at 8 / 4 / 2 bits, out[3..5] where L / r does.
+namespace {
+constexpr uint32_t kSelftestFirst = 0x0d800000u;  // 2^-100
+constexpr uint32_t kSelftestEnd = 0x7f800000u;    // +infinity, not included
+
+__device__ __forceinline__ bool same_float(float a, float b) { return __float_as_uint(a) == __float_as_uint(b); }
+
+template <int BITS>
+__device__ __forceinline__ void selftest_one(float r, unsigned& bad_scale, unsigned& bad_inv) {
+  constexpr float L = float((1 << BITS) - 1);
+  // the divisor and dividend reach the divisions through an opaque copy so that no rewrite can merge the two sides
+  float ro = r, Lo = L;
+  asm volatile("" : "+v"(ro), "+v"(Lo));
+  bad_scale += same_float(range_over_levels<BITS>(r), ro / Lo) ? 0u : 1u;
+  bad_inv += same_float(levels_over_range<BITS>(r), Lo / ro) ? 0u : 1u;
+}
+
+__global__ void __launch_bounds__(kBlockThreads) selftest_division_kernel(unsigned long long* out) {
+  unsigned bad[6] = {0, 0, 0, 0, 0, 0};
+  const uint64_t stride = (uint64_t)gridDim.x * kBlockThreads;
+  for (uint64_t u = kSelftestFirst + (uint64_t)blockIdx.x * kBlockThreads + threadIdx.x; u < kSelftestEnd; u += stride) {
+    const float r = __uint_as_float((uint32_t)u);
+    selftest_one<8>(r, bad[0], bad[3]);
+    selftest_one<4>(r, bad[1], bad[4]);
+    selftest_one<2>(r, bad[2], bad[5]);
+  }
+#pragma unroll
+  for (int k = 0; k < 6; ++k)
+    if (bad[k] != 0) atomicAdd(&out[k], (unsigned long long)bad[k]);
+}
+}  // namespace
+
+static int launch_selftest_division(unsigned long long* mismatches_dev, hipStream_t stream) {
+  hipLaunchKernelGGL(selftest_division_kernel, dim3(8192), dim3(kBlockThreads), 0, stream, mismatches_dev);
+  return hipGetLastError() == hipSuccess ? KVH_OK : KVH_E_HIP;
+}
+
 extern "C" {
 
 int kvh_num_levels(void) { return 3; }
@@ -430,6 +470,12 @@ int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int rea
     case 8 * 16 + 1: return launch_stream<8, 1>(dst_dev, src_dev, n_units, s);
     default: return KVH_E_ARG;
   }
+}
+
+int kvh_selftest_division(uint64_t* mismatches_dev, void* stream) {
+  if (mismatches_dev == nullptr || (reinterpret_cast<uintptr_t>(mismatches_dev) & 7u) != 0) return KVH_E_ARG;
+  return launch_selftest_division(reinterpret_cast<unsigned long long*>(mismatches_dev),
+                                  static_cast<hipStream_t>(stream));
 }
 
 const char* kvh_strerror(int status) {

@@ -114,6 +114,31 @@ __device__ __forceinline__ T sload(const void* p) {
   return *reinterpret_cast<const __attribute__((address_space(4))) T*>(reinterpret_cast<uintptr_t>(p));
 }
 
+// ---- the two quotients of a group -------------------------------------------------------------
+// scale = r / L and inv = L / r are defined as correctly rounded fp32 divisions.  The IEEE division sequence costs
+// about eleven instructions; the forms below cost four (a reciprocal, a product, the exact residual by one fma, one
+// corrected quotient by another) and return the same bits for every range a group of finite values can have, at
+// L = 3, 15, 255.  That is a property of this chip's reciprocal instruction, established by running all of those
+// ranges through both forms and both divisions (kvh_selftest_division does it in about a second, and the GPU tests
+// call it).
+template <int BITS>
+__device__ __forceinline__ float range_over_levels(float r) {  // r / L
+  constexpr float L = float((1 << BITS) - 1);
+  constexpr float kInvL = 1.0f / L;
+  const float q = r * kInvL;
+  return __builtin_fmaf(__builtin_fmaf(-q, L, r), kInvL, q);
+}
+template <int BITS>
+__device__ __forceinline__ float levels_over_range(float r) {  // L / r, r >= 2^-100
+  // everything runs on r / 16 and L / 16 (exact scalings that leave the quotient as it is): the reciprocal of a range
+  // near the top of fp32 would be subnormal otherwise
+  constexpr float L16 = float((1 << BITS) - 1) * 0x1p-4f;
+  const float rr = r * 0x1p-4f;
+  const float y = __builtin_amdgcn_rcpf(rr);
+  const float q = L16 * y;
+  return __builtin_fmaf(__builtin_fmaf(-q, rr, L16), y, q);
+}
+
 // ---- group parameters -------------------------------------------------------------------------
 // meta = mn | mx << 16 (raw 16-bit patterns as stored in the blob).
 struct GroupParams {
@@ -124,21 +149,19 @@ struct GroupParams {
 
 template <int DT, int BITS>
 __device__ __forceinline__ GroupParams decode_params(uint32_t meta) {
-  constexpr float L = float((1 << BITS) - 1);
   GroupParams p;
   p.mn = t16_to_f32<DT>(meta & 0xffffu);
   float r = t16_to_f32<DT>(meta >> 16) - p.mn;
   bool degenerate = r < 0x1p-100f;
-  p.scale = degenerate ? 0.0f : r / L;  // IEEE division (correctly rounded)
+  p.scale = degenerate ? 0.0f : range_over_levels<BITS>(r);
   p.top = degenerate ? (meta & 0xffffu) : (meta >> 16);
   return p;
 }
 
 template <int BITS>
 __device__ __forceinline__ float encode_inv(float mn, float mx) {
-  constexpr float L = float((1 << BITS) - 1);
   float r = mx - mn;
-  return r < 0x1p-100f ? 0.0f : L / r;
+  return r < 0x1p-100f ? 0.0f : levels_over_range<BITS>(r);
 }
 
 // ---- kernel parameter blocks and launchers (defined next to their kernels) -----------------------

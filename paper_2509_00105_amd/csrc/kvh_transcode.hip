@@ -203,8 +203,8 @@ __device__ __forceinline__ TcParams tc_params(uint32_t meta, uint32_t& out_meta,
   p.mn = t16_to_f32<DT>(mn_bits);
   const float r = t16_to_f32<DT>(mx_bits) - p.mn;
   const bool degenerate = r < 0x1p-100f;
-  p.scale = degenerate ? 0.0f : r / LI;  // IEEE divisions (correctly rounded)
-  p.inv = degenerate ? 0.0f : LO / r;
+  p.scale = degenerate ? 0.0f : range_over_levels<BI>(r);  // correctly rounded quotients
+  p.inv = degenerate ? 0.0f : levels_over_range<BO>(r);
   const uint32_t top_bits = degenerate ? mn_bits : mx_bits;
   p.top = t16_to_f32<DT>(top_bits);
   out_meta = mn_bits | top_bits << 16;
