@@ -418,8 +418,12 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
 }
 
 // grid = (64-row blocks x spans, 2 * l, items); span fastest; wave w of a block takes rows 8 w .. 8 w + 7 of its 64.
+// Waves per SIMD the register allocation is held to (0 = compiler's choice).  The kernel needs 93 registers, which
+// would let two blocks (16 waves) share a CU; the write stream does better with fewer waves in flight.  Measured on
+// the 8K-token shape, 8 / 4 / 2 bits, % of HBM peak in the benchmark's rotation: 16 waves per CU 68.4 / 71.6 / 71.3,
+// this setting (allocation raised to three waves per SIMD) 70.4 / 73.8 / 74.5, two waves per SIMD 71.0 / 69.2 / 67.1.
 #ifndef KVH_DEC_WPE
-#define KVH_DEC_WPE 0  // waves per SIMD the register allocation is held to (0 = compiler's choice)
+#define KVH_DEC_WPE 3
 #endif
 #if KVH_DEC_WPE
 #define KVH_DEC_OCC __attribute__((amdgpu_waves_per_eu(KVH_DEC_WPE, KVH_DEC_WPE)))
