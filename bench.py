@@ -11,10 +11,10 @@ Prints ONE JSON line: the whole-step throughput in GB/s of uncompressed KV, per-
 figures, the HBM roofline of the dominant kernel (algorithmic bytes / HIP-event duration) and
 the CPU oracle timed on the host cores over a bounded sample of the same workload.  After the
 timed region the same run also measures, as extra keys of that line: what the memory system
-gives plain read / fill / copy / mixed streams (`memory_probes`), the streamed chunk-by-chunk
-forms of the headline workload, and decode on the other workload shapes (`other_workloads`:
-Llama-3-70B-shaped 32K tokens, a 128K-token context streamed and batched, and a mixed batch of
-64 requests decoded into a paged cache).
+gives plain read / fill / copy / mixed streams (`memory_probes`), the headline workload through the
+calls that take host-side descriptors and as one launch per chunk (`chunked_and_per_chunk`), and decode
+on the other workload shapes (`other_workloads`: Llama-3-70B-shaped 32K tokens, a 128K-token context
+through the chunked and the batched calls, and a mixed batch of 64 requests decoded into a paged cache).
 """
 from __future__ import annotations
 
@@ -183,8 +183,8 @@ def memory_probes(torch, kvh, stream, src, dst):
 
 def other_workloads(torch, np, gen, kvh, stream, reps=5):
     """Decode (and encode, for context) on the other workload shapes, each tensor generated once and freed before the
-    next: Llama-3-70B-shaped 32K tokens at every level; a 128K-token context at 8 and 2 bits, streamed (one launch
-    per chunk, one stream, one synchronisation) and batched; 64 requests of mixed lengths with a level per chunk,
+    next: Llama-3-70B-shaped 32K tokens at every level; a 128K-token context at 8 and 2 bits through the chunked calls
+    (host-side descriptors, 32 chunks per launch) and the batched ones; 64 requests of mixed lengths with a level per chunk,
     decoded by ONE batched launch into a paged cache through permuted page tables."""
     dev = torch.device("cuda:0")
     res = {}
@@ -221,7 +221,7 @@ def other_workloads(torch, np, gen, kvh, stream, reps=5):
                                  "uncompressed_bytes": unc, "levels": rows}
         del kv, out
 
-        # ---- 128K-token context, 256-token chunks: streamed and batched ----
+        # ---- 128K-token context, 256-token chunks: host-side descriptors (chunked calls) and batched ----
         cfg = gen.CONFIGS["long_7b_128k"]
         l, N, c, chunk = cfg.l, cfg.n, cfg.c, cfg.chunk
         kv = gen.make_kv_device(l, N, c, cfg.dtype, cfg.seed, device=dev)
@@ -240,16 +240,17 @@ def other_workloads(torch, np, gen, kvh, stream, reps=5):
             ds = time_reps(torch, stream, lambda: kvh.decode_chunked(blobs, offs, levels, chunk, N, out[0], out[1], status=st, stream=stream), reps)
             db = time_reps(torch, stream, lambda: kvh.decode_batch(di, len(spans), chunk, out[0], out[1], status=st, stream=stream), reps)
             assert int(st.abs().sum().item()) == 0
-            row = {"bits": kvh.level_bits(level), "decode_streamed": rate_fields(ds, unc, blobs.numel()),
+            row = {"bits": kvh.level_bits(level), "decode_chunked": rate_fields(ds, unc, blobs.numel()),
                    "decode_batch": rate_fields(db, unc, blobs.numel()),
-                   "encode_streamed": rate_fields(es, unc, blobs.numel()), "encode_batch": rate_fields(eb, unc, blobs.numel())}
-            row["decode_streamed"]["us_per_launch"] = ds["avg_ms"] * 1e3 / len(spans)
-            row["decode_streamed"]["launch_overhead_vs_batch"] = ds["avg_ms"] / db["avg_ms"] - 1.0
+                   "encode_chunked": rate_fields(es, unc, blobs.numel()), "encode_batch": rate_fields(eb, unc, blobs.numel())}
+            row["decode_chunked"]["launches"] = -(-len(spans) // 32)
+            row["decode_chunked"]["vs_batch"] = ds["avg_ms"] / db["avg_ms"] - 1.0
             rows.append(row)
             del blobs
         res["long_7b_128k"] = {"workload": cfg.name, "chunks": N // chunk, "chunk_tokens": chunk, "uncompressed_bytes": unc,
-                               "streamed_form": "one kvh_decode launch per chunk (kvh_decode_chunked), one stream, one "
-                                                "synchronisation at the end", "levels": rows}
+                               "chunked_form": "kvh_decode_chunked / kvh_encode_chunked: host arrays of offsets and levels, "
+                                               "32 chunks per launch through the kernel arguments, one stream, one "
+                                               "synchronisation at the end", "levels": rows}
         del kv, out
 
         # ---- 64 requests of mixed lengths, a level per chunk, paged destination ----
@@ -402,9 +403,12 @@ def main():
     copy_gbps = 5 * 2 * (1 << 30) / pe[0].elapsed_time(pe[1]) / 1e6
     probes = None if args.no_extras else memory_probes(torch, kvh, stream, probe_src, probe_dst)
 
-    # Outside the timed region: the streamed forms of the same workload — one launch per chunk (kvh_encode_chunked /
-    # kvh_decode_chunked: 32 launches back to back on one stream, one synchronisation at the end), against the one
-    # batched launch the timed region uses.
+    # Outside the timed region: the same workload through the calls that take host-side descriptors
+    # (kvh_encode_chunked / kvh_decode_chunked carry them in the kernel arguments, 32 chunks per launch, so config 2 is
+    # one launch) and, for the record, as one launch per chunk (kvh_decode / kvh_encode per chunk, 32 launches back to
+    # back on one stream, one synchronisation at the end): enqueued from Python (`host_enqueue_ms` is what the
+    # interpreter needs to issue them; when it exceeds the GPU time the figure is the host's) and replayed from a
+    # captured HIP graph, which takes the host out of it.
     streamed = []
     if not args.no_extras:
         with torch.cuda.stream(stream):
@@ -417,10 +421,45 @@ def main():
                                                                         status=status[level], stream=stream), 10)
                 e = time_reps(torch, stream, lambda: kvh.encode_chunked(kv[0], kv[1], chunk, lv, blobs[level], offs,
                                                                         stream=stream), 10)
+                pieces = [blobs[level][o:o + size_of[level]] for o in offs]
+                ksrc = [kv[0][:, i * chunk:(i + 1) * chunk] for i in range(n_chunks)]
+                vsrc = [kv[1][:, i * chunk:(i + 1) * chunk] for i in range(n_chunks)]
+                sts = [status[level][i:i + 1] for i in range(n_chunks)]
+
+                def dec_each():
+                    for i in range(n_chunks):
+                        kvh.decode(pieces[i], level, chunk, out[0], out[1], dst_token0=i * chunk, status=sts[i], stream=stream)
+
+                def enc_each():
+                    for i in range(n_chunks):
+                        kvh.encode(ksrc[i], vsrc[i], level, blob=pieces[i], stream=stream)
+
+                row = {"bits": kvh.level_bits(level), "chunks": n_chunks,
+                       "launches_chunked": -(-n_chunks // 32),
+                       "decode_chunked": rate_fields(d, 2 * l * N * c * 2, blobs[level].numel()),
+                       "encode_chunked": rate_fields(e, 2 * l * N * c * 2, blobs[level].numel())}
+                for name, fn in (("decode_per_chunk_launch", dec_each), ("encode_per_chunk_launch", enc_each)):
+                    t = rate_fields(time_reps(torch, stream, fn, 10), 2 * l * N * c * 2, blobs[level].numel())
+                    torch.cuda.synchronize()
+                    h0 = time.perf_counter()
+                    fn()
+                    t["host_enqueue_ms"] = (time.perf_counter() - h0) * 1e3
+                    torch.cuda.synchronize()
+                    try:
+                        graph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(graph, stream=stream):
+                            fn()
+                        g = rate_fields(time_reps(torch, stream, graph.replay, 10), 2 * l * N * c * 2, blobs[level].numel())
+                        t["graph_replay"] = {"avg_ms": g["avg_ms"], "hbm_frac": g["hbm_frac"],
+                                             "us_per_launch": g["avg_ms"] * 1e3 / n_chunks}
+                        del graph
+                    except Exception as ex:  # a capture the runtime refuses leaves the eager figures standing
+                        t["graph_replay"] = None
+                        t["graph_error"] = repr(ex)[:200]
+                    t["us_per_launch"] = t["avg_ms"] * 1e3 / n_chunks
+                    row[name] = t
                 assert int(status[level].abs().sum().item()) == 0
-                u_, b_ = 2 * l * N * c * 2, blobs[level].numel()
-                streamed.append({"bits": kvh.level_bits(level), "launches": n_chunks,
-                                 "decode_streamed": rate_fields(d, u_, b_), "encode_streamed": rate_fields(e, u_, b_)})
+                streamed.append(row)
 
     # Outside the timed region: the raw level (an entry stored in full quality: rows copied into and out of the blob),
     # one batched launch over the 32 chunks in each direction.
@@ -672,7 +711,7 @@ def main():
                           "profiles/codec_kernels_llama3_8b_8k_bf16.md (counters cannot be read inside this run)",
         "copy_probe_GBps": copy_gbps,
         "memory_probes": probes,
-        "streamed_chunk_by_chunk": streamed,
+        "chunked_and_per_chunk": streamed,
         "raw_level": raw_level,
         "other_workloads": others,
         "token_dropping": dropping,

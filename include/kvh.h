@@ -103,7 +103,8 @@ int kvh_encode(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int lev
  * tokens [i*chunk, min(N, (i+1)*chunk)), is encoded at levels[i] and written at
  * (char*)blobs_dev + blob_offsets[i].  `levels` and `blob_offsets` are HOST arrays of
  * ceil(N/chunk) entries; offsets must be multiples of 16 and every blob must end at or before
- * `cap`.  chunk must be a multiple of 128.  One kernel launch per chunk, all asynchronous on
+ * `cap`.  chunk must be a multiple of 128.  The descriptors travel in the kernel arguments, 32
+ * chunks per launch (the library owns no device memory to put them in), all asynchronous on
  * `stream`. */
 int kvh_encode_chunked(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c, int chunk, const int8_t* levels,
                        void* blobs_dev, const size_t* blob_offsets, size_t cap, void* stream);
@@ -137,12 +138,13 @@ int kvh_encode_batch(const kvh_enc_item* items_dev, int n_items, int max_tokens_
 int kvh_decode(const void* blob_dev, kvh_dtype dt, int l, int n_tokens, int c, int level, const kvh_kv_view* dst,
                int64_t dst_token0, const int32_t* page_table_dev, int block_tokens, int32_t* status_dev, void* stream);
 
-/* Decompress a long entry chunk by chunk, streamed (the mirror of kvh_encode_chunked): chunk i holds tokens
+/* Decompress a long entry chunk by chunk (the mirror of kvh_encode_chunked): chunk i holds tokens
  * [i*chunk, min(N, (i+1)*chunk)), was stored at levels[i], starts at (char*)blobs_dev + blob_offsets[i] and goes to
  * logical positions dst_token0 + i*chunk onward of `dst` (contiguous or paged, as kvh_decode).  `levels` and
  * `blob_offsets` are HOST arrays of ceil(N/chunk) entries; offsets must be multiples of 16.  status_dev, if not
- * NULL, has one zeroed int32 per chunk.  One kernel launch per chunk, all asynchronous on `stream`, no
- * synchronisation in between: the first chunks can be consumed while later ones are still being decoded. */
+ * NULL, has one zeroed int32 per chunk.  32 chunks per kernel launch (descriptors in the kernel arguments), all
+ * asynchronous on `stream`, no synchronisation in between; a caller whose chunks arrive one at a time calls
+ * kvh_decode per chunk instead. */
 int kvh_decode_chunked(const void* blobs_dev, const size_t* blob_offsets, const int8_t* levels, kvh_dtype dt, int l, int N,
                        int c, int chunk, const kvh_kv_view* dst, int64_t dst_token0, const int32_t* page_table_dev,
                        int block_tokens, int32_t* status_dev, void* stream);

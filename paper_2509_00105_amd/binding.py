@@ -195,7 +195,7 @@ def encode(k: torch.Tensor, v: torch.Tensor, level: int, blob: torch.Tensor | No
 
 def encode_chunked(k: torch.Tensor, v: torch.Tensor, chunk: int, levels, blobs: torch.Tensor, blob_offsets,
                    stream=None) -> None:
-    """kvh_encode_chunked: one launch per chunk, blobs written at the given byte offsets of `blobs`."""
+    """kvh_encode_chunked: chunk blobs written at the given byte offsets of `blobs` (host-side descriptors)."""
     view, dt = _view(k, v)
     _require_cuda(blobs)
     l, N, c = k.shape
@@ -255,7 +255,7 @@ def decode(blob: torch.Tensor, level: int, n_tokens: int, k_dst: torch.Tensor, v
 def decode_chunked(blobs: torch.Tensor, blob_offsets, levels, chunk: int, n_tokens: int, k_dst: torch.Tensor,
                    v_dst: torch.Tensor, dst_token0: int = 0, page_table: torch.Tensor | None = None,
                    block_tokens: int = 16, status: torch.Tensor | None = None, stream=None) -> None:
-    """kvh_decode_chunked: one launch per chunk of an n_tokens entry whose blobs sit at the given byte offsets."""
+    """kvh_decode_chunked: an n_tokens entry whose chunk blobs sit at the given byte offsets (host-side descriptors)."""
     paged = page_table is not None
     view, dt = _view(k_dst, v_dst, paged)
     _require_cuda(blobs, page_table, status)

@@ -197,10 +197,16 @@ int kvh_encode_chunked(const kvh_kv_view* kv, kvh_dtype dt, int l, int N, int c,
   a.l = l;
   a.c = c;
   a.split = kNoSplit;
-  for (int i = 0; i < n_chunks; ++i) {
-    const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
-    a.one = kvh_enc_item{static_cast<uint8_t*>(blobs_dev) + blob_offsets[i], (int64_t)i * chunk, n, levels[i]};
-    if (int rc = launch_encode(a, dt, 1, n, static_cast<hipStream_t>(stream))) return rc;
+  // the descriptors ride in the kernel arguments, kInlineItems chunks per launch
+  for (int i0 = 0; i0 < n_chunks; i0 += kInlineItems) {
+    const int cnt = n_chunks - i0 < kInlineItems ? n_chunks - i0 : kInlineItems;
+    for (int j = 0; j < cnt; ++j) {
+      const int i = i0 + j;
+      const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
+      a.inline_items[j] = kvh_enc_item{static_cast<uint8_t*>(blobs_dev) + blob_offsets[i], (int64_t)i * chunk, n, levels[i]};
+    }
+    a.n_inline = cnt;
+    if (int rc = launch_encode(a, dt, cnt, chunk, static_cast<hipStream_t>(stream))) return rc;
   }
   return KVH_OK;
 }
@@ -273,12 +279,18 @@ int kvh_decode_chunked(const void* blobs_dev, const size_t* blob_offsets, const 
   a.c = c;
   a.block_tokens = page_table_dev != nullptr ? block_tokens : 1;
   a.split = kNoSplit;
-  for (int i = 0; i < n_chunks; ++i) {
-    const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
-    a.one = kvh_item{static_cast<const uint8_t*>(blobs_dev) + blob_offsets[i], n, levels[i],
-                     dst_token0 + (int64_t)i * chunk, page_table_dev};
-    a.status = status_dev != nullptr ? status_dev + i : nullptr;
-    if (int rc = launch_decode(a, dt, 1, n, static_cast<hipStream_t>(stream))) return rc;
+  // the descriptors ride in the kernel arguments, kInlineItems chunks per launch
+  for (int i0 = 0; i0 < n_chunks; i0 += kInlineItems) {
+    const int cnt = n_chunks - i0 < kInlineItems ? n_chunks - i0 : kInlineItems;
+    for (int j = 0; j < cnt; ++j) {
+      const int i = i0 + j;
+      const int n = (i + 1) * (int64_t)chunk <= N ? chunk : N - i * chunk;
+      a.inline_items[j] = kvh_item{static_cast<const uint8_t*>(blobs_dev) + blob_offsets[i], n, levels[i],
+                                   dst_token0 + (int64_t)i * chunk, page_table_dev};
+    }
+    a.n_inline = cnt;
+    a.status = status_dev != nullptr ? status_dev + i0 : nullptr;
+    if (int rc = launch_decode(a, dt, cnt, chunk, static_cast<hipStream_t>(stream))) return rc;
   }
   return KVH_OK;
 }

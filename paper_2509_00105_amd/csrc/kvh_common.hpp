@@ -165,8 +165,12 @@ __device__ __forceinline__ float encode_inv(float mn, float mx) {
 }
 
 // ---- kernel parameter blocks and launchers (defined next to their kernels) -----------------------
+// Jobs that travel inside the kernel arguments: the chunked calls have their descriptors in host arrays, and
+// this many per launch reach the kernel without any device memory of the library's own.
+constexpr int kInlineItems = 32;
+
 struct DecodeParams {
-  const kvh_item* items;  // device array of jobs, or nullptr: decode `one`
+  const kvh_item* items;  // device array of jobs, or nullptr: decode `one` (or the inline jobs)
   const kvh_kept_item* kept_items;  // device array of jobs that may be token-dropped (then `items` is nullptr)
   kvh_item one;
   uint16_t* k;
@@ -181,10 +185,12 @@ struct DecodeParams {
   int32_t split;
   int64_t jump;
   uint32_t hdr_orig_tokens, hdr_sink, hdr_window;
+  int n_inline;  // > 0: the jobs are inline_items[0 .. n_inline), read from the kernel-argument segment
+  kvh_item inline_items[kInlineItems];
 };
 
 struct EncodeParams {
-  const kvh_enc_item* items;  // device array of jobs, or nullptr: encode `one`
+  const kvh_enc_item* items;  // device array of jobs, or nullptr: encode `one` (or the inline jobs)
   const kvh_kept_enc_item* kept_items;  // device array of token-dropping jobs (then `items` is nullptr)
   kvh_enc_item one;
   const uint16_t* k;
@@ -197,7 +203,13 @@ struct EncodeParams {
   int32_t split;
   int64_t jump;
   uint32_t hdr_orig_tokens, hdr_sink, hdr_window;
+  int n_inline;  // > 0: the jobs are inline_items[0 .. n_inline), read from the kernel-argument segment
+  kvh_enc_item inline_items[kInlineItems];
 };
+
+// Address of a member of the kernel's (single, by-value) parameter block inside the kernel-argument segment.
+#define KVH_KERNARG_MEMBER(TYPE, MEMBER) \
+  (reinterpret_cast<uintptr_t>(__builtin_amdgcn_kernarg_segment_ptr()) + offsetof(TYPE, MEMBER))
 
 constexpr int32_t kNoSplit = 0x7fffffff;
 

@@ -444,8 +444,10 @@ __global__ __launch_bounds__(kDecThreads) KVH_DEC_OCC void decode_kernel(DecodeP
   kvh_item it;
   DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
   bool consistent = true;
-  if (a.items != nullptr) {
-    const uint8_t* p = reinterpret_cast<const uint8_t*>(a.items + item_idx);
+  const kvh_item* items = a.items;
+  if (a.n_inline > 0) items = reinterpret_cast<const kvh_item*>(KVH_KERNARG_MEMBER(DecodeParams, inline_items));
+  if (items != nullptr) {
+    const uint8_t* p = reinterpret_cast<const uint8_t*>(items + item_idx);
 #if KVH_SCALAR_DESC
     uintx4 lo = sload<uintx4>(p), hi = sload<uintx4>(p + 16);
 #else

@@ -346,8 +346,10 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   __shared__ float red[2 * kEncWaves * kStripCh];  // 32 KiB
   kvh_enc_item it;
   DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
-  if (a.items != nullptr) {
-    const kvh_enc_item* p = a.items + blockIdx.z;
+  const kvh_enc_item* items = a.items;
+  if (a.n_inline > 0) items = reinterpret_cast<const kvh_enc_item*>(KVH_KERNARG_MEMBER(EncodeParams, inline_items));
+  if (items != nullptr) {
+    const kvh_enc_item* p = items + blockIdx.z;
 #if KVH_SCALAR_DESC
     uintx4 lo = sload<uintx4>(p);
     uintx2 hi = sload<uintx2>(reinterpret_cast<const uint8_t*>(p) + 16);

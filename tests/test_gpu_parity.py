@@ -217,7 +217,7 @@ def test_chunked_and_batched_encode_match_per_chunk_oracle(kvh):
     kvh.decode_batch(ditems, 4, chunk, ok, ov, status=status)
     torch.cuda.synchronize()
     assert not status.any()
-    # the streamed form: one launch per chunk from the same host arrays, at a token offset, contiguous and paged
+    # the chunked form: the same host arrays as descriptors, at a token offset, contiguous and paged
     base, bt = 32, 16
     sk = torch.zeros((l, base + N + 7, c), dtype=torch.float16, device="cuda"); sv = torch.zeros_like(sk)
     status.zero_()

@@ -161,7 +161,7 @@ def test_config4_long_context_streamed_decode(kvh):
         batched = decode_all(kvh, blobs, spans, levels, offs, chunk, torch.empty_like(kv))
         streamed = torch.empty_like(kv)
         status = torch.zeros(n_chunks, dtype=torch.int32, device="cuda")
-        kvh.decode_chunked(blobs, offs, levels, chunk, N, streamed[0], streamed[1], status=status)   # chunk by chunk, never synchronising
+        kvh.decode_chunked(blobs, offs, levels, chunk, N, streamed[0], streamed[1], status=status)   # host-side descriptors, 32 chunks per launch
         torch.cuda.synchronize()
         assert int(status.abs().sum().item()) == 0
         assert torch.equal(streamed.view(torch.int16), batched.view(torch.int16))
