@@ -163,6 +163,31 @@ def rate_fields(t, unc_bytes, blob_bytes):
     return t
 
 
+def per_chunk_launches(torch, kvh, stream, fn, n_launches, unc_bytes, blob_bytes, reps):
+    """One launch per chunk, back to back on one stream, one synchronisation: timed as issued from Python
+    (`host_enqueue_ms` = what the interpreter needs to issue them; where it exceeds the GPU time the figure is the
+    host's) and replayed from a captured HIP graph, which takes the host out of it."""
+    t = rate_fields(time_reps(torch, stream, fn, reps), unc_bytes, blob_bytes)
+    t["launches"] = n_launches
+    t["us_per_launch"] = t["avg_ms"] * 1e3 / n_launches
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
+    fn()
+    t["host_enqueue_ms"] = (time.perf_counter() - h0) * 1e3
+    torch.cuda.synchronize()
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            fn()
+        g = rate_fields(time_reps(torch, stream, graph.replay, reps), unc_bytes, blob_bytes)
+        t["graph_replay"] = {"avg_ms": g["avg_ms"], "hbm_frac": g["hbm_frac"], "us_per_launch": g["avg_ms"] * 1e3 / n_launches}
+        del graph
+    except Exception as ex:  # a capture the runtime refuses leaves the eager figures standing
+        t["graph_replay"] = None
+        t["graph_error"] = repr(ex)[:200]
+    return t
+
+
 def memory_probes(torch, kvh, stream, src, dst):
     """Plain streams over 1 GiB buffers: what this device gives a pure read, a pure fill, a copy, and streams with
     the codec's read : write mixes and no arithmetic.  GB/s counts bytes read plus bytes written."""
@@ -239,12 +264,22 @@ def other_workloads(torch, np, gen, kvh, stream, reps=5):
             eb = time_reps(torch, stream, lambda: kvh.encode_batch(ei, len(spans), chunk, kv[0], kv[1], stream=stream), reps)
             ds = time_reps(torch, stream, lambda: kvh.decode_chunked(blobs, offs, levels, chunk, N, out[0], out[1], status=st, stream=stream), reps)
             db = time_reps(torch, stream, lambda: kvh.decode_batch(di, len(spans), chunk, out[0], out[1], status=st, stream=stream), reps)
+            pieces = [blobs[int(o):int(o) + sz] for o, sz in zip(offs, sizes)]
+            sts = [st[i:i + 1] for i in range(len(spans))]
+
+            def dec_each():
+                for i, (t0, n) in enumerate(spans):
+                    kvh.decode(pieces[i], level, n, out[0], out[1], dst_token0=t0, status=sts[i], stream=stream)
+
+            dp = per_chunk_launches(torch, kvh, stream, dec_each, len(spans), unc, blobs.numel(), 3)
             assert int(st.abs().sum().item()) == 0
             row = {"bits": kvh.level_bits(level), "decode_chunked": rate_fields(ds, unc, blobs.numel()),
+                   "decode_per_chunk_launch": dp,
                    "decode_batch": rate_fields(db, unc, blobs.numel()),
                    "encode_chunked": rate_fields(es, unc, blobs.numel()), "encode_batch": rate_fields(eb, unc, blobs.numel())}
             row["decode_chunked"]["launches"] = -(-len(spans) // 32)
             row["decode_chunked"]["vs_batch"] = ds["avg_ms"] / db["avg_ms"] - 1.0
+            dp["launch_overhead_vs_batch"] = dp["avg_ms"] / db["avg_ms"] - 1.0
             rows.append(row)
             del blobs
         res["long_7b_128k"] = {"workload": cfg.name, "chunks": N // chunk, "chunk_tokens": chunk, "uncompressed_bytes": unc,
@@ -439,25 +474,7 @@ def main():
                        "decode_chunked": rate_fields(d, 2 * l * N * c * 2, blobs[level].numel()),
                        "encode_chunked": rate_fields(e, 2 * l * N * c * 2, blobs[level].numel())}
                 for name, fn in (("decode_per_chunk_launch", dec_each), ("encode_per_chunk_launch", enc_each)):
-                    t = rate_fields(time_reps(torch, stream, fn, 10), 2 * l * N * c * 2, blobs[level].numel())
-                    torch.cuda.synchronize()
-                    h0 = time.perf_counter()
-                    fn()
-                    t["host_enqueue_ms"] = (time.perf_counter() - h0) * 1e3
-                    torch.cuda.synchronize()
-                    try:
-                        graph = torch.cuda.CUDAGraph()
-                        with torch.cuda.graph(graph, stream=stream):
-                            fn()
-                        g = rate_fields(time_reps(torch, stream, graph.replay, 10), 2 * l * N * c * 2, blobs[level].numel())
-                        t["graph_replay"] = {"avg_ms": g["avg_ms"], "hbm_frac": g["hbm_frac"],
-                                             "us_per_launch": g["avg_ms"] * 1e3 / n_chunks}
-                        del graph
-                    except Exception as ex:  # a capture the runtime refuses leaves the eager figures standing
-                        t["graph_replay"] = None
-                        t["graph_error"] = repr(ex)[:200]
-                    t["us_per_launch"] = t["avg_ms"] * 1e3 / n_chunks
-                    row[name] = t
+                    row[name] = per_chunk_launches(torch, kvh, stream, fn, n_chunks, 2 * l * N * c * 2, blobs[level].numel(), 10)
                 assert int(status[level].abs().sum().item()) == 0
                 streamed.append(row)
 
