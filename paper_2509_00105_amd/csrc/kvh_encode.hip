@@ -38,6 +38,19 @@ __device__ __forceinline__ void gstore(void* p, T v) {
 #ifndef KVH_ENC_NTL
 #define KVH_ENC_NTL 1  // non-temporal loads of the 16-bit rows
 #endif
+// Rows of a V wave whose statistics are reduced together (16, 8, 4 or 2), per code width.  Fewer operations with
+// larger batches, earlier stores with smaller ones; measured on the 8K-token shape (% of HBM peak at 8 / 4 / 2 bits:
+// batches of 16: 72.7 / 74.0 / 71.4, of 8: 71.8 / 73.8 / 69.6, of 4: 73.1 / 73.8 / 76.3, of 2: 72.4 / 76.7 / 69.0; one
+// all-reduce per row, the form before: 73.1 / 73.9 / 69.2), and the choice below holds on the other shapes.
+#ifndef KVH_ENC_VBATCH8
+#define KVH_ENC_VBATCH8 4
+#endif
+#ifndef KVH_ENC_VBATCH4
+#define KVH_ENC_VBATCH4 2
+#endif
+#ifndef KVH_ENC_VBATCH2
+#define KVH_ENC_VBATCH2 4
+#endif
 template <typename T>
 __device__ __forceinline__ T gload_rows(const void* p) {
 #if KVH_ENC_NTL
@@ -259,21 +272,103 @@ __device__ __forceinline__ void encode_raw_block(const EncodeParams& a, const kv
   }
 }
 
-// all-reduce over the 16 lanes of a DPP row (= one head): rotate by 8, 4, 2, 1 and combine
-template <bool IS_MIN>
-__device__ __forceinline__ float row16_reduce(float v) {
-#define KVH_ROR_STEP(CTRL)                                                                          \
-  {                                                                                                 \
-    float o = __builtin_bit_cast(                                                                   \
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false)); \
-    v = IS_MIN ? __builtin_fminf(v, o) : __builtin_fmaxf(v, o);                                     \
+// ---- V statistics: a reduce-scatter over the 16 lanes of a head --------------------------------------
+// A wave holds 16 rows; a head is one DPP row of 16 lanes.  Instead of an all-reduce per row (after which all 16
+// lanes would prepare the same parameters 16 times over), the 16 per-row partials of a lane are folded in four
+// halving steps so that lane j of a head ends up with the minimum and maximum of row j alone: 15 combine-and-select
+// steps per lane for all 16 rows, parameters prepared once per (row, head), and row i's two parameters fetched
+// back by every lane with a row broadcast when row i is quantised.
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+constexpr int kDppRor8 = 0x128;    // row_ror:8, lane L reads lane L - 8 (mod 16): its partner across bit 3
+constexpr int kDppPlus4 = 0x12C;   // row_ror:12, lane L reads lane L + 4 (mod 16)
+constexpr int kDppMinus4 = 0x124;  // row_ror:4, lane L reads lane L - 4 (mod 16)
+constexpr int kDppXor2 = 0x4E;     // quad_perm [2,3,0,1]
+constexpr int kDppXor1 = 0xB1;     // quad_perm [1,0,3,2]
+constexpr int kDppRowBcast = 0x150;  // + i: every lane of a row reads lane i of that row
+
+// One fold.  p0 and p1 are this lane's partials of two rows that differ in the row-index bit which the lane bit
+// `bit` decides: the lane keeps the row whose bit equals its own and folds in its partner's partial of that row.
+// FROM_UP reads the partner of a lane whose bit is clear, FROM_DOWN that of a lane whose bit is set; each is only
+// right for its half of the lanes, and the select takes the right one.
+template <bool IS_MIN, int FROM_UP, int FROM_DOWN>
+__device__ __forceinline__ float fold16(float p0, float p1, bool bit) {
+  const float a = dpp_f<FROM_UP>(p0), b = dpp_f<FROM_DOWN>(p1);
+  const float lo = IS_MIN ? __builtin_fminf(a, p0) : __builtin_fmaxf(a, p0);
+  const float hi = IS_MIN ? __builtin_fminf(b, p1) : __builtin_fmaxf(b, p1);
+  return bit ? hi : lo;
+}
+// A batch of R rows (16, 8 or 4).  in[k] = this lane's partial of rows 2k / 2k + 1 of the batch, already folded over
+// lane bit 0 (so in[k] belongs to row 2k + (lane & 1)).  The remaining row-index bits are folded over lane bits
+// 1 .. log2(R) - 1; over the lane bits above that the partials are all-reduced, so that the full reduction of row r
+// ends up in every lane with (lane & (R - 1)) == r, lane r among them.
+template <bool IS_MIN, int R>
+__device__ __forceinline__ float reduce_scatter(const float (&in)[R / 2], int lane) {
+  auto both = [](float v, float o) { return IS_MIN ? __builtin_fminf(v, o) : __builtin_fmaxf(v, o); };
+  if constexpr (R == 16) {
+    float c[4], e[2];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) c[m] = fold16<IS_MIN, kDppXor2, kDppXor2>(in[2 * m], in[2 * m + 1], (lane & 2) != 0);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) e[q] = fold16<IS_MIN, kDppPlus4, kDppMinus4>(c[2 * q], c[2 * q + 1], (lane & 4) != 0);
+    return fold16<IS_MIN, kDppRor8, kDppRor8>(e[0], e[1], (lane & 8) != 0);
+  } else if constexpr (R == 8) {
+    float c[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) c[m] = fold16<IS_MIN, kDppXor2, kDppXor2>(in[2 * m], in[2 * m + 1], (lane & 2) != 0);
+    const float e = fold16<IS_MIN, kDppPlus4, kDppMinus4>(c[0], c[1], (lane & 4) != 0);
+    return both(dpp_f<kDppRor8>(e), e);
+  } else if constexpr (R == 4) {
+    float c = fold16<IS_MIN, kDppXor2, kDppXor2>(in[0], in[1], (lane & 2) != 0);
+    c = both(dpp_f<kDppMinus4>(c), c);
+    return both(dpp_f<kDppRor8>(c), c);
+  } else {
+    static_assert(R == 2, "batches of 16, 8, 4 or 2 rows");
+    float c = both(dpp_f<kDppXor2>(in[0]), in[0]);
+    c = both(dpp_f<kDppMinus4>(c), c);
+    return both(dpp_f<kDppRor8>(c), c);
   }
-  KVH_ROR_STEP(0x128)  // row_ror:8
-  KVH_ROR_STEP(0x124)  // row_ror:4
-  KVH_ROR_STEP(0x122)  // row_ror:2
-  KVH_ROR_STEP(0x121)  // row_ror:1
-#undef KVH_ROR_STEP
-  return v;
+}
+
+// Minimum and maximum of the 8 values of one lane and row.  For bf16 the upper halves are compared as they sit in
+// their words: the lower half only extends the mantissa, which never carries a value past its 16-bit neighbour, so
+// the upper 16 bits of the result are those of the true extreme (the sign of a zero aside, which the metadata
+// drops anyway).
+template <int DT>
+__device__ __forceinline__ void row_minmax(const uintx4& d, float& mn, float& mx) {
+  if constexpr (DT == KVH_BF16) {
+    // (the words are copied out first: a bit cast applied to a vector element directly reads element 0)
+    const uint32_t w0 = d.x, w1 = d.y, w2 = d.z, w3 = d.w;
+    const float h0 = __builtin_bit_cast(float, w0), h1 = __builtin_bit_cast(float, w1);
+    const float h2 = __builtin_bit_cast(float, w2), h3 = __builtin_bit_cast(float, w3);
+    const float l0 = __builtin_bit_cast(float, w0 << 16), l1 = __builtin_bit_cast(float, w1 << 16);
+    const float l2 = __builtin_bit_cast(float, w2 << 16), l3 = __builtin_bit_cast(float, w3 << 16);
+    mn = __builtin_fminf(__builtin_fminf(h0, h1), h2);
+    mx = __builtin_fmaxf(__builtin_fmaxf(h0, h1), h2);
+    mn = __builtin_fminf(__builtin_fminf(mn, h3), l0);
+    mx = __builtin_fmaxf(__builtin_fmaxf(mx, h3), l0);
+    mn = __builtin_fminf(__builtin_fminf(mn, l1), l2);
+    mx = __builtin_fmaxf(__builtin_fmaxf(mx, l1), l2);
+    mn = __builtin_fminf(mn, l3);
+    mx = __builtin_fmaxf(mx, l3);
+  } else {
+    float x[8];
+    unpack8<DT>(d, x);
+    mn = __builtin_fminf(__builtin_fminf(x[0], x[1]), x[2]);
+    mx = __builtin_fmaxf(__builtin_fmaxf(x[0], x[1]), x[2]);
+    mn = __builtin_fminf(__builtin_fminf(mn, x[3]), x[4]);
+    mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[3]), x[4]);
+    mn = __builtin_fminf(__builtin_fminf(mn, x[5]), x[6]);
+    mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[5]), x[6]);
+    mn = __builtin_fminf(mn, x[7]);
+    mx = __builtin_fmaxf(mx, x[7]);
+  }
 }
 
 template <int DT, int BITS>
@@ -303,34 +398,54 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
       t = t < n ? t : n - 1;
       d[i] = gload_rows<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
     }
+    // The 16 rows are taken in batches of R, in the order their loads return: statistics of a batch, its metadata
+    // words and parameters (lane r of a head takes row r of the batch), then its rows are quantised and stored
+    // while the loads of the next batch are still arriving.
+    constexpr int R = BITS == 8 ? KVH_ENC_VBATCH8 : BITS == 4 ? KVH_ENC_VBATCH4 : KVH_ENC_VBATCH2;
+    static_assert(kEncRows % R == 0 && (R == 16 || R == 8 || R == 4 || R == 2), "batches of 16, 8, 4 or 2 rows");
+    auto batch = [&](auto b_idx) {
+      constexpr int r0 = decltype(b_idx)::value * R;
+      float pmn[R / 2], pmx[R / 2];
 #pragma unroll
-    for (int i = 0; i < kEncRows; ++i) {
-      int t = t_first + i;
-      float x[8];
-      unpack8<DT>(d[i], x);
-      float mn = __builtin_fminf(__builtin_fminf(x[0], x[1]), x[2]);
-      float mx = __builtin_fmaxf(__builtin_fmaxf(x[0], x[1]), x[2]);
-      mn = __builtin_fminf(__builtin_fminf(mn, x[3]), x[4]);
-      mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[3]), x[4]);
-      mn = __builtin_fminf(__builtin_fminf(mn, x[5]), x[6]);
-      mx = __builtin_fmaxf(__builtin_fmaxf(mx, x[5]), x[6]);
-      mn = __builtin_fminf(mn, x[7]);
-      mx = __builtin_fmaxf(mx, x[7]);
-      mn = row16_reduce<true>(mn);
-      mx = row16_reduce<false>(mx);
-      if (t < n) {  // wave-uniform; the row addresses are formed on the scalar unit, outside the per-lane test
-        uint8_t* meta_row = uniform(vmeta + (size_t)t * heads * 4);
-        uint8_t* code_row = uniform(codes + (size_t)t * geo.row_bytes);
-        if (active) {
-          uint32_t lo = exact_bits<DT>(mn), hi = exact_bits<DT>(mx);
-          if ((lane & 15) == 0) gstore<uint32_t>(meta_row + (ch0 / kGroup) * 4, lo | hi << 16);
-          float2 par;
-          par.x = t16_to_f32<DT>(lo);
-          par.y = encode_inv<BITS>(par.x, t16_to_f32<DT>(hi));
-          quantise_store8<BITS>(code_row + lane_code_off, x, [&](int) { return par; });
-        }
+      for (int k = 0; k < R / 2; ++k) {
+        float mn0, mx0, mn1, mx1;
+        row_minmax<DT>(d[r0 + 2 * k], mn0, mx0);
+        row_minmax<DT>(d[r0 + 2 * k + 1], mn1, mx1);
+        pmn[k] = fold16<true, kDppXor1, kDppXor1>(mn0, mn1, (lane & 1) != 0);
+        pmx[k] = fold16<false, kDppXor1, kDppXor1>(mx0, mx1, (lane & 1) != 0);
       }
-    }
+      const float mn_own = reduce_scatter<true, R>(pmn, lane);
+      const float mx_own = reduce_scatter<false, R>(pmx, lane);
+      const uint32_t lo = exact_bits<DT>(mn_own), hi = exact_bits<DT>(mx_own);
+      const int t_own = t_first + r0 + (lane & (R - 1));
+      if (active && (lane & 15) < R && t_own < n)
+        gstore<uint32_t>(vmeta + ((size_t)t_own * heads + ch0 / kGroup) * 4, lo | hi << 16);
+      float2 own;
+      own.x = t16_to_f32<DT>(lo);
+      own.y = encode_inv<BITS>(own.x, t16_to_f32<DT>(hi));
+      auto row = [&](auto idx) {
+        constexpr int r = decltype(idx)::value;
+        constexpr int i = r0 + r;
+        const int t = t_first + i;
+        if (t < n) {  // wave-uniform; the row address is formed on the scalar unit, outside the per-lane test
+          uint8_t* code_row = uniform(codes + (size_t)t * geo.row_bytes);
+          float2 par;
+          par.x = dpp_f<kDppRowBcast + r>(own.x);
+          par.y = dpp_f<kDppRowBcast + r>(own.y);
+          if (active) {
+            // the row is unpacked a second time here; the copy below keeps the compiler from holding the first
+            // unpacking of all rows in registers instead (which spills)
+            uintx4 w = d[i];
+            asm volatile("" : "+v"(w));
+            float x[8];
+            unpack8<DT>(w, x);
+            quantise_store8<BITS>(code_row + lane_code_off, x, [&](int) { return par; });
+          }
+        }
+      };
+      for_each_index(row, std::make_integer_sequence<int, R>{});
+    };
+    for_each_index(batch, std::make_integer_sequence<int, kEncRows / R>{});
   }
   // zero the padding that rounds the vmeta section up to 16 bytes
   if (strip == 0 && threadIdx.x == 0 && (tile + 1) * kEncTile >= n) {
