@@ -8,7 +8,8 @@ launch (6 kernels, 6 GiB of uncompressed KV through the codec per step).  Inputs
 outputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line: the whole-step throughput in GB/s of uncompressed KV, per-kernel
-figures, the HBM roofline of the dominant kernel (algorithmic bytes / HIP-event duration) and
+figures, the HBM roofline of the dominant kernel (algorithmic bytes / duration between the two HIP
+events the kernel itself records at its start and end) and
 the CPU oracle timed on the host cores over a bounded sample of the same workload.  After the
 timed region the same run also measures, as extra keys of that line: what the memory system
 gives plain read / fill / copy / mixed streams (`memory_probes`), the headline workload through the
@@ -377,14 +378,24 @@ def main():
             for kind, level in kernels:
                 launch(kind, level)
         torch.cuda.synchronize()
-        # timed region: exactly `steps` steps; every kernel is bracketed by events on its own stream
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(kernels) + 1)] for _ in range(args.steps)]
+        # timed region: exactly `steps` steps.  A step is bracketed by two events on the launch stream; each kernel
+        # carries its own pair, recorded by the kernel itself at its start and end (kvh_time_next_launch), so that a
+        # kernel's duration is what a kernel trace shows and no event packets sit between the launches of a step.
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        kev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in kernels]
+               for _ in range(args.steps)]
+        for row in kev:  # torch creates an event at its first record
+            for a_, b_ in row:
+                a_.record(stream)
+                b_.record(stream)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(args.steps):
             ev[s][0].record(stream)
             for j, (kind, level) in enumerate(kernels):
+                kvh.time_next_launch(*kev[s][j])
                 launch(kind, level)
-                ev[s][j + 1].record(stream)
+            ev[s][1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
 
@@ -537,12 +548,17 @@ def main():
         tc_status[(a, b)] = torch.zeros(n_chunks, dtype=torch.int32, device=dev)
     tc_reps = 10
     with torch.cuda.stream(stream):
-        tev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(tc_pairs) + 1)] for _ in range(tc_reps + 1)]
+        tev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in tc_pairs]
+               for _ in range(tc_reps + 1)]
+        for row in tev:
+            for a_, b_ in row:
+                a_.record(stream)
+                b_.record(stream)
+        torch.cuda.synchronize()
         for r in range(tc_reps + 1):  # rep 0 is the warm-up
-            tev[r][0].record(stream)
             for j, pr in enumerate(tc_pairs):
+                kvh.time_next_launch(*tev[r][j])
                 kvh.transcode_batch(tc_items[pr], n_chunks, chunk, tdt, l, c, status=tc_status[pr], stream=stream)
-                tev[r][j + 1].record(stream)
         torch.cuda.synchronize()
     assert all(int(tc_status[pr].abs().sum().item()) == 0 for pr in tc_pairs), "a transcode reported a header mismatch"
 
@@ -671,7 +687,7 @@ def main():
               "placed": {"tier%d" % t: {str(b): int(((p_tier == t) & (p_choice == j)).sum()) for j, b in enumerate((16, 8, 4, 2))}
                          for t in range(2)},
               "evicted": int((p_tier < 0).sum())}
-    step_ms = [ev[s][0].elapsed_time(ev[s][-1]) for s in range(args.steps)]
+    step_ms = [ev[s][0].elapsed_time(ev[s][1]) for s in range(args.steps)]
     total_ms = ev[0][0].elapsed_time(ev[-1][-1])
     ms_per_step = total_ms / args.steps
     unc = 2 * l * N * c * 2
@@ -679,7 +695,7 @@ def main():
     per_kernel = []
     for j, (kind, level) in enumerate(kernels):
         bits = kvh.level_bits(level)
-        durs = [ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(args.steps)]
+        durs = [kev[s][j][0].elapsed_time(kev[s][j][1]) for s in range(args.steps)]
         avg = sum(durs) / len(durs)
         u, b = algorithmic_bytes(l, N, c, bits, n_chunks, chunk)
         per_kernel.append({"kernel": "%s_kernel" % kind, "op": kind, "bits": bits, "avg_ms": avg, "min_ms": min(durs),
@@ -691,7 +707,7 @@ def main():
     by_op = {(r["op"], r["bits"]): r["avg_ms"] for r in per_kernel}
     transcode = []
     for j, (a, b) in enumerate(tc_pairs):
-        durs = [tev[r][j].elapsed_time(tev[r][j + 1]) for r in range(1, tc_reps + 1)]
+        durs = [tev[r][j][0].elapsed_time(tev[r][j][1]) for r in range(1, tc_reps + 1)]
         avg = sum(durs) / len(durs)
         ba, bb = kvh.level_bits(a), kvh.level_bits(b)
         moved = blobs[a].numel() + tc_out[(a, b)].numel()

@@ -379,6 +379,15 @@ int kvh_copy_probe(void* dst_dev, const void* src_dev, size_t bytes, void* strea
 int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int reads_per_unit, int writes_per_unit,
                      void* stream);
 
+/* Timing of one launch, for callers that profile (not part of the codec; Design section, Estimator: the decompression
+ * overhead of an entry is something to be measured).  The two events (hipEvent_t, created by the caller with timing
+ * enabled) are recorded by the NEXT encode, decode or transcode kernel that this host thread launches through the
+ * library: `start_event` when that kernel starts executing, `stop_event` when it has finished, on the launch's
+ * stream, so that hipEventElapsedTime(start, stop) is the kernel's own duration - what a kernel trace reports -
+ * without the queue packets that events recorded around a launch put between neighbouring kernels.  The pair is
+ * used once and forgotten; a call that launches several kernels times its first.  Errors: KVH_E_ARG (null event). */
+int kvh_time_next_launch(void* start_event, void* stop_event);
+
 /* Self-test of the arithmetic shortcut behind the group parameters (Sec. 3.2's quantisation: scale = r / L and
  * inv = L / r are correctly rounded fp32 quotients).  The kernels form both with a reciprocal and two fused
  * corrections instead of the division sequence; that this returns the division's bits is a property of the

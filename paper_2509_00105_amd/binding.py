@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
         L.kvh_copy_probe.argtypes = [vp, vp, sz, vp]
         L.kvh_stream_probe.restype = i32
         L.kvh_stream_probe.argtypes = [vp, vp, sz, i32, i32, vp]
+        L.kvh_time_next_launch.restype = i32
+        L.kvh_time_next_launch.argtypes = [vp, vp]
         L.kvh_selftest_division.restype = i32
         L.kvh_selftest_division.argtypes = [vp, vp]
         L.kvh_decode_chunked.restype = i32
@@ -545,6 +547,16 @@ def stream_probe(dst: torch.Tensor, src: torch.Tensor, n_units: int, reads_per_u
         raise ValueError("buffers too small for this many units")
     _check(lib().kvh_stream_probe(dst.data_ptr(), src.data_ptr(), n_units, reads_per_unit, writes_per_unit,
                                   _stream_ptr(stream)), "kvh_stream_probe")
+
+
+def time_next_launch(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> None:
+    """kvh_time_next_launch: the next encode / decode / transcode kernel launched from this thread records `start`
+    at its own start and `stop` at its end (events created with enable_timing=True and recorded once before, so
+    that they exist; read them with start.elapsed_time(stop) after synchronising)."""
+    hs, he = int(start.cuda_event), int(stop.cuda_event)
+    if hs == 0 or he == 0:
+        raise ValueError("record each event once before handing it over: torch creates an event at its first record")
+    _check(lib().kvh_time_next_launch(hs, he), "kvh_time_next_launch")
 
 
 def selftest_division(stream=None) -> list:

@@ -138,6 +138,17 @@ static int launch_selftest_division(unsigned long long* mismatches_dev, hipStrea
   return hipGetLastError() == hipSuccess ? KVH_OK : KVH_E_HIP;
 }
 
+namespace kvh {
+namespace {
+thread_local TimingEvents t_timing = {nullptr, nullptr};
+}
+TimingEvents take_timing_events() {
+  const TimingEvents ev = t_timing;
+  t_timing = TimingEvents{nullptr, nullptr};
+  return ev;
+}
+}  // namespace kvh
+
 extern "C" {
 
 int kvh_num_levels(void) { return 3; }
@@ -482,6 +493,12 @@ int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int rea
     case 8 * 16 + 1: return launch_stream<8, 1>(dst_dev, src_dev, n_units, s);
     default: return KVH_E_ARG;
   }
+}
+
+int kvh_time_next_launch(void* start_event, void* stop_event) {
+  if (start_event == nullptr || stop_event == nullptr) return KVH_E_ARG;
+  kvh::t_timing = kvh::TimingEvents{static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+  return KVH_OK;
 }
 
 int kvh_selftest_division(uint64_t* mismatches_dev, void* stream) {

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/kvh.h"
@@ -232,6 +233,24 @@ struct TranscodeParams {
 int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
 int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
 int launch_transcode(const TranscodeParams& a, int dt, int n_items, int max_tokens, hipStream_t stream);
+
+// Launch timing.  A caller that wants the duration of one launch itself (not of the launch plus the queue
+// packets that bracketing events add around it) hands over two events with kvh_time_next_launch; the next kernel
+// this thread launches through launch_kernel records them at its own start and end.
+struct TimingEvents {
+  hipEvent_t start, stop;
+};
+TimingEvents take_timing_events();  // the pair set for this thread, cleared by the call
+
+template <typename... Args>
+inline void launch_kernel(void (*kernel)(Args...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t stream,
+                          Args... args) {
+  const TimingEvents ev = take_timing_events();
+  if (ev.start != nullptr || ev.stop != nullptr)
+    hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ev.start, ev.stop, 0u, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+}
 
 #define KVH_HIP_CHECK_LAUNCH()                          \
   do {                                                  \

@@ -531,9 +531,9 @@ int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hi
   // planes of the call lie within 1 GiB of each other and costs 3-4 % when they span 4 GiB or more.
   b.planes_first = (int64_t)a.l * a.layer_stride * 2 <= ((int64_t)1 << 29) ? 1 : 0;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0, stream, b);
+    launch_kernel(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0u, stream, b);
   else
-    hipLaunchKernelGGL(decode_kernel<KVH_BF16>, grid, dim3(kDecThreads), 0, stream, b);
+    launch_kernel(decode_kernel<KVH_BF16>, grid, dim3(kDecThreads), 0u, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

@@ -577,9 +577,9 @@ int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hi
   EncodeParams b = a;
   b.max_tokens = max_tokens;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(encode_kernel<KVH_F16>, grid, dim3(kEncThreads), 0, stream, b);
+    launch_kernel(encode_kernel<KVH_F16>, grid, dim3(kEncThreads), 0u, stream, b);
   else
-    hipLaunchKernelGGL(encode_kernel<KVH_BF16>, grid, dim3(kEncThreads), 0, stream, b);
+    launch_kernel(encode_kernel<KVH_BF16>, grid, dim3(kEncThreads), 0u, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

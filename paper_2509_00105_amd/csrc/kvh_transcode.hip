@@ -808,9 +808,9 @@ int launch_transcode(const TranscodeParams& a, int dt, int n_items, int max_toke
   TranscodeParams b = a;
   b.max_tokens = max_tokens;
   if (dt == KVH_F16)
-    hipLaunchKernelGGL(transcode_kernel<KVH_F16>, grid, dim3(kTcThreads), 0, stream, b);
+    launch_kernel(transcode_kernel<KVH_F16>, grid, dim3(kTcThreads), 0u, stream, b);
   else
-    hipLaunchKernelGGL(transcode_kernel<KVH_BF16>, grid, dim3(kTcThreads), 0, stream, b);
+    launch_kernel(transcode_kernel<KVH_BF16>, grid, dim3(kTcThreads), 0u, stream, b);
   KVH_HIP_CHECK_LAUNCH();
   return KVH_OK;
 }

@@ -59,3 +59,28 @@ def test_stream_probe_moves_what_it_says(kvh):
         kvh.stream_probe(dst, src, 100, 1, 1)                 # not whole groups of 256 units
     with pytest.raises(ValueError):
         kvh.stream_probe(dst[:64], src, 256, 1, 1)            # destination too small
+
+
+def test_time_next_launch_records_the_kernel_itself(kvh):
+    """kvh_time_next_launch: the pair is recorded by the next kernel only, its span is positive and no longer than
+    what events recorded around the same launch see."""
+    k = torch.randn(8, 2048, 1024, device="cuda").to(torch.bfloat16)
+    v = torch.randn_like(k)
+    blob = kvh.encode(k, v, 0)
+    torch.cuda.synchronize()
+    s = torch.cuda.current_stream()
+    a, b, x, y = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+    for e in (a, b, x, y):
+        e.record(s)
+    torch.cuda.synchronize()
+    x.record(s)
+    kvh.time_next_launch(a, b)
+    kvh.encode(k, v, 0, blob=blob)
+    y.record(s)
+    torch.cuda.synchronize()
+    own, around = a.elapsed_time(b), x.elapsed_time(y)
+    assert 0.0 < own <= around * 1.02 + 0.002, (own, around)
+    kvh.encode(k, v, 0, blob=blob)          # no pair pending: this launch must leave the events alone
+    torch.cuda.synchronize()
+    assert a.elapsed_time(b) == own
+    assert kvh.lib().kvh_time_next_launch(None, None) == -1
