@@ -38,18 +38,11 @@ __device__ __forceinline__ void gstore(void* p, T v) {
 #ifndef KVH_ENC_NTL
 #define KVH_ENC_NTL 1  // non-temporal loads of the 16-bit rows
 #endif
-// Rows of a V wave whose statistics are reduced together (16, 8, 4 or 2), per code width.  Fewer operations with
-// larger batches, earlier stores with smaller ones; measured on the 8K-token shape (% of HBM peak at 8 / 4 / 2 bits:
-// batches of 16: 72.7 / 74.0 / 71.4, of 8: 71.8 / 73.8 / 69.6, of 4: 73.1 / 73.8 / 76.3, of 2: 72.4 / 76.7 / 69.0; one
-// all-reduce per row, the form before: 73.1 / 73.9 / 69.2), and the choice below holds on the other shapes.
-#ifndef KVH_ENC_VBATCH8
-#define KVH_ENC_VBATCH8 4
-#endif
-#ifndef KVH_ENC_VBATCH4
-#define KVH_ENC_VBATCH4 2
-#endif
-#ifndef KVH_ENC_VBATCH2
-#define KVH_ENC_VBATCH2 4
+// Rows of a V wave whose statistics are reduced together (16, 8, 4 or 2).  Fewer operations with larger batches,
+// earlier stores with smaller ones; measured on the 8K-token shape (% of HBM peak at 8 / 4 / 2 bits): batches of 16:
+// 76.2 / 76.5 / 75.8, of 8: 76.1 / 76.3 / 75.8, of 4: 76.6 / 78.0 / 77.6, of 2: 77.2 / 77.9 / 75.1.
+#ifndef KVH_ENC_VBATCH
+#define KVH_ENC_VBATCH 4
 #endif
 template <typename T>
 __device__ __forceinline__ T gload_rows(const void* p) {
@@ -158,29 +151,55 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
     d[i] = gload_rows<uintx4>(uniform(src + (it.src_token0 + t + (t >= split ? jump : 0)) * a.token_stride * 2) + lane_src_off);
   }
   float mn[8], mx[8];
-  unpack8<DT>(d[0], mn);
+  if constexpr (DT == KVH_BF16) {
+    // bf16: the odd channels (upper halves) are compared in their words as they are, the even ones after a shift;
+    // the lower half of a word only extends the mantissa and never carries a value past its 16-bit neighbour
+    auto word = [&](int i, int q) { return q == 0 ? d[i].x : q == 1 ? d[i].y : q == 2 ? d[i].z : d[i].w; };
+    auto as_f = [](uint32_t w) { return __builtin_bit_cast(float, w); };
 #pragma unroll
-  for (int j = 0; j < 8; ++j) mx[j] = mn[j];
-  {
-    float x1[8];
-    unpack8<DT>(d[1], x1);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      mn[j] = __builtin_fminf(mn[j], x1[j]);
-      mx[j] = __builtin_fmaxf(mx[j], x1[j]);
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t w0 = word(0, q), w1 = word(1, q);
+      mn[2 * q] = __builtin_fminf(as_f(w0 << 16), as_f(w1 << 16));
+      mx[2 * q] = __builtin_fmaxf(as_f(w0 << 16), as_f(w1 << 16));
+      mn[2 * q + 1] = __builtin_fminf(as_f(w0), as_f(w1));
+      mx[2 * q + 1] = __builtin_fmaxf(as_f(w0), as_f(w1));
     }
-  }
 #pragma unroll
-  for (int i = 2; i < kEncRows; i += 2) {  // two rows per step: three-operand min / max
-    float x0[8], x1[8];
-    unpack8<DT>(d[i], x0);
-    unpack8<DT>(d[i + 1], x1);
+    for (int i = 2; i < kEncRows; i += 2) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      mn[j] = __builtin_fminf(__builtin_fminf(mn[j], x0[j]), x1[j]);
-      mx[j] = __builtin_fmaxf(__builtin_fmaxf(mx[j], x0[j]), x1[j]);
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t w0 = word(i, q), w1 = word(i + 1, q);
+        mn[2 * q] = __builtin_fminf(__builtin_fminf(mn[2 * q], as_f(w0 << 16)), as_f(w1 << 16));
+        mx[2 * q] = __builtin_fmaxf(__builtin_fmaxf(mx[2 * q], as_f(w0 << 16)), as_f(w1 << 16));
+        mn[2 * q + 1] = __builtin_fminf(__builtin_fminf(mn[2 * q + 1], as_f(w0)), as_f(w1));
+        mx[2 * q + 1] = __builtin_fmaxf(__builtin_fmaxf(mx[2 * q + 1], as_f(w0)), as_f(w1));
+      }
     }
-    __builtin_amdgcn_sched_barrier(0);  // keep the unpacked floats of different rows from piling up in registers
+  } else {
+    unpack8<DT>(d[0], mn);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mx[j] = mn[j];
+    {
+      float x1[8];
+      unpack8<DT>(d[1], x1);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        mn[j] = __builtin_fminf(mn[j], x1[j]);
+        mx[j] = __builtin_fmaxf(mx[j], x1[j]);
+      }
+    }
+#pragma unroll
+    for (int i = 2; i < kEncRows; i += 2) {  // two rows per step: three-operand min / max
+      float x0[8], x1[8];
+      unpack8<DT>(d[i], x0);
+      unpack8<DT>(d[i + 1], x1);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        mn[j] = __builtin_fminf(__builtin_fminf(mn[j], x0[j]), x1[j]);
+        mx[j] = __builtin_fmaxf(__builtin_fmaxf(mx[j], x0[j]), x1[j]);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep the unpacked floats of different rows from piling up in registers
+    }
   }
   // red[0][wave][512] = partial minima, red[1][wave][512] = partial maxima
   float* rmn = red + (0 * kEncWaves + wave) * kStripCh + lane * kLaneCh;
@@ -221,6 +240,12 @@ __device__ __forceinline__ void encode_k_block(const EncodeParams& a, const kvh_
     meta[j] = lo | hi << 16;
     par[j].x = t16_to_f32<DT>(lo);
     par[j].y = encode_inv<BITS>(par[j].x, t16_to_f32<DT>(hi));
+    // The eight channels are independent, and the scheduler would interleave them all, which costs more registers
+    // than the kernel has left here (the 16 rows stay in registers across this point).  Spilled registers come back
+    // through loads in the middle of the store loop, and a wait for such a load also waits for every store issued
+    // before it: 3-5 such stalls per block, 3 points of throughput.  The empty statement ties the next channel's
+    // inputs to this channel's results, so the channels are prepared one after the other and nothing spills.
+    if (j + 1 < 8) asm volatile("" : "+v"(par[j].x), "+v"(par[j].y), "+v"(meta[j]), "+v"(mn[j + 1]), "+v"(mx[j + 1]));
   }
   if (!active) return;
   if (wave == 0) {
@@ -401,7 +426,7 @@ __device__ __forceinline__ void encode_v_block(const EncodeParams& a, const kvh_
     // The 16 rows are taken in batches of R, in the order their loads return: statistics of a batch, its metadata
     // words and parameters (lane r of a head takes row r of the batch), then its rows are quantised and stored
     // while the loads of the next batch are still arriving.
-    constexpr int R = BITS == 8 ? KVH_ENC_VBATCH8 : BITS == 4 ? KVH_ENC_VBATCH4 : KVH_ENC_VBATCH2;
+    constexpr int R = KVH_ENC_VBATCH;
     static_assert(kEncRows % R == 0 && (R == 16 || R == 8 || R == 4 || R == 2), "batches of 16, 8, 4 or 2 rows");
     auto batch = [&](auto b_idx) {
       constexpr int r0 = decltype(b_idx)::value * R;
