@@ -204,10 +204,11 @@ def test_transcode_argument_errors(kvh):
 
 @pytest.mark.parametrize("dt", [F16, BF16])
 @pytest.mark.parametrize("mix", ["offset", "offset+constant", "offset+tiny"])
-def test_transcode_8_to_2_away_from_zero(kvh, mix, dt):
+def test_transcode_from_8_bits_away_from_zero(kvh, mix, dt):
     """Groups that sit far from zero compared with their range: the rounding to the 16-bit type then moves the steps
     of the 8 -> 2 code map off 43 / 128 / 213 (for bf16 in a good share of the groups), which is the case the fitted
-    form of the map exists for; constant channels add degenerate groups to such blocks, and channels whose range is
+    form of the map exists for, and those of the 8 -> 4 map off the places of q / 17 (no shortcut may assume them
+    there); constant channels add degenerate groups to such blocks, and channels whose range is
     a few units in the last place add groups that no polynomial is accepted for.  All must equal the oracle."""
     l, n, c = 2, 300, 1024
     rng = np.random.default_rng(77 + dt)
@@ -234,9 +235,16 @@ def test_transcode_8_to_2_away_from_zero(kvh, mix, dt):
         q2 = np.stack([(raw2 >> (2 * i)) & 3 for i in range(4)], axis=2).reshape(128, c)
         moved = ((q8 + 42) * 772 >> 16) != q2        # the standard map: steps at 43, 128, 213
         assert moved.any(axis=0).mean() > 0.005
-    want = oracle.transcode(src, dt, l, n, c, 0, 2)
-    status = torch.zeros(1, dtype=torch.int32, device="cuda")
-    got = kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, 0, 2, status=status)
-    torch.cuda.synchronize()
-    assert status.item() == 0
-    assert_same_blob(got.cpu().numpy(), want, "8 -> 2, %s" % mix)
+        # the same for 8 -> 4: its steps do not lie where those of q / 17 lie either
+        four = oracle.encode(wk, wk, dt, 1)
+        off1 = oracle.section_offsets(l, n, c, 1, 0)
+        raw4 = four[off1["kcodes"]:off1["kcodes"] + 128 * c // 2].reshape(128, c // 2)
+        q4 = np.stack([raw4 & 15, raw4 >> 4], axis=2).reshape(128, c)
+        assert (((q8 * 15 + 127) // 255) != q4).any(axis=0).mean() > 0.005
+    for lo in (2, 1):
+        want = oracle.transcode(src, dt, l, n, c, 0, lo)
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        got = kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, 0, lo, status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        assert_same_blob(got.cpu().numpy(), want, "8 -> %d, %s" % (kvh.level_bits(lo), mix))
