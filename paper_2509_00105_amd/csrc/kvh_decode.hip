@@ -241,6 +241,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   // no wave waits for another.  Measured on the 8K-token shape, shared / own: 71.0 / 72.1 % at 8 bits, 74.6 / 73.5 % at
   // 4 bits, 75.1 / 75.6 % at 2 bits.
   constexpr bool kOwnK = KVH_DEC_KOWN < 0 ? BITS != 4 : KVH_DEC_KOWN != 0;
+  static_assert(!kOwnK || kDecSub == 1, "the own-parameter form takes one unit per wave");
   // K metadata: the channels of the span this thread prepares for the whole block
   uint32_t kwords[kDecPrep] = {};
   const int pc = span * kDecSpanCh + (int)threadIdx.x * kDecPrep;
