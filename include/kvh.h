@@ -385,7 +385,8 @@ int kvh_stream_probe(void* dst_dev, const void* src_dev, size_t n_units, int rea
  * library: `start_event` when that kernel starts executing, `stop_event` when it has finished, on the launch's
  * stream, so that hipEventElapsedTime(start, stop) is the kernel's own duration - what a kernel trace reports -
  * without the queue packets that events recorded around a launch put between neighbouring kernels.  The pair is
- * used once and forgotten; a call that launches several kernels times its first.  Errors: KVH_E_ARG (null event). */
+ * used once and forgotten; a call that launches several kernels times its first, and a call that is refused
+ * before it launches anything leaves the pair waiting for the next launch.  Errors: KVH_E_ARG (null event). */
 int kvh_time_next_launch(void* start_event, void* stop_event);
 
 /* Self-test of the arithmetic shortcut behind the group parameters (Sec. 3.2's quantisation: scale = r / L and

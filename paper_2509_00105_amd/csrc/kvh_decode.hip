@@ -64,15 +64,35 @@ __device__ __forceinline__ T gload_stream(const uint8_t* p) {
 #endif
 }
 
+// 16-byte store of decoded values, never re-read by this kernel: non-temporal.  With THROUGH the store also carries
+// device scope (sc1), which makes the L2 pass the line on at once instead of holding it until it is evicted; the
+// data written is the same.  Which levels gain from it is measured, see kStoreThrough below.  (The builtin has no
+// form with both hints, hence the instruction is spelled out; it costs the immediate offsets the compiler would
+// otherwise fold, two additions per store.  The s_nop is the wait state this chip family wants between a store of more
+// than 8 bytes and a write to the registers that held its data; the compiler inserts it after its own stores and
+// cannot see into this one.)
+#ifndef KVH_DEC_THROUGH
+#define KVH_DEC_THROUGH -1  // device-scope stores: 1 always, 0 never, -1 per code width
+#endif
+template <bool THROUGH>
 __device__ __forceinline__ void gstore16(uint16_t* p, const uint4& v) {
   auto* g = reinterpret_cast<__attribute__((address_space(1))) uintx4*>(reinterpret_cast<uintptr_t>(p));
   uintx4 x = {v.x, v.y, v.z, v.w};
+  if constexpr (THROUGH) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(g), "v"(x) : "memory");
+  } else {
 #if KVH_DEC_NT
-  __builtin_nontemporal_store(x, g);
+    __builtin_nontemporal_store(x, g);
 #else
-  *g = x;
+    *g = x;
 #endif
+  }
 }
+// Six shapes from 1 to 16 GiB (8K to 128K tokens, 32 and 80 layers), % of HBM peak, plain / device-scope stores, each
+// with the better K-parameter form: 8 bits 70.8 / 73.4 on average (better on every shape, +1.3 to +3.3), 4 bits
+// 73.4 / 76.8 (every shape, +0.9 to +6.2), 2 bits 73.9 / 74.0 (from -5 on the 8K shape to +3).
+template <int BITS>
+constexpr bool kStoreThrough = KVH_DEC_THROUGH < 0 ? (BITS == 8 || BITS == 4) : KVH_DEC_THROUGH != 0;
 
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
@@ -238,9 +258,10 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
   // K parameters, one of two ways.  Shared: every thread of the block prepares kDecPrep channels of the span, the
   // results meet in LDS behind one barrier.  Own: every wave prepares the 16 channels of each of its lanes itself
   // (8 times the arithmetic, which the short quotient forms made cheap, and 8 times the metadata reads, from L2), and
-  // no wave waits for another.  Measured on the 8K-token shape, shared / own: 71.0 / 72.1 % at 8 bits, 74.6 / 73.5 % at
-  // 4 bits, 75.1 / 75.6 % at 2 bits.
-  constexpr bool kOwnK = KVH_DEC_KOWN < 0 ? BITS != 4 : KVH_DEC_KOWN != 0;
+  // no wave waits for another.  Which is faster depends on the level and on the store form; average over the six
+  // shapes named at kStoreThrough, shared / own: 8 bits (device-scope stores) 73.4 / 72.4 %, 4 bits (device-scope)
+  // 73.0 / 76.8 %, 2 bits (plain non-temporal) 73.0 / 73.9 %.
+  constexpr bool kOwnK = KVH_DEC_KOWN < 0 ? BITS != 8 : KVH_DEC_KOWN != 0;
   static_assert(!kOwnK || kDecSub == 1, "the own-parameter form takes one unit per wave");
   // K metadata: the channels of the span this thread prepares for the whole block
   uint32_t kwords[kDecPrep] = {};
@@ -286,7 +307,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
 #pragma unroll
         for (int s = 0; s < kDecSegs; ++s) {
           uint4 out = dequant8<DT, BITS, FIX>(cw[i][s], param_of(i, s));
-          if (active[s]) gstore16(row + ch[s], out);
+          if (active[s]) gstore16<kStoreThrough<BITS>>(row + ch[s], out);
         }
       }
     }
@@ -451,7 +472,7 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
         uint16_t* row = dst + (int64_t)r * a.token_stride;
 #pragma unroll
         for (int s = 0; s < kDecSegs; ++s)
-          if (active[s]) gstore16(row + ch[s], make_uint4(d[i][s].x, d[i][s].y, d[i][s].z, d[i][s].w));
+          if (active[s]) gstore16<kStoreThrough<16>>(row + ch[s], make_uint4(d[i][s].x, d[i][s].y, d[i][s].z, d[i][s].w));
       }
     }
   }
