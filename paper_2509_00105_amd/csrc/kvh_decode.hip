@@ -166,13 +166,20 @@ __device__ __forceinline__ uint4 dequant8(const Codes<BITS>& cw, P&& param) {
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// Physical row of logical position s.
-__device__ __forceinline__ int32_t physical_row(int64_t s, const int32_t* page_table, int block_tokens) {
-  if (page_table == nullptr) return (int32_t)s;
+// Physical row of logical position s, in two halves: row = entry * block_tokens + rest.  The page-table entry is
+// only requested here; the product is formed by the caller after the unit's other loads have been issued, so that
+// the first use of the entry does not hold them back by one trip to memory (a multiplication right behind the load
+// makes the wave wait for it before it requests its codes).  Without a page table entry = 0 and rest = s.
+struct RowRef {
+  int32_t entry, rest;
+};
+__device__ __forceinline__ RowRef physical_row(int64_t s, const int32_t* page_table, int block_tokens) {
+  if (page_table == nullptr) return {0, (int32_t)s};
   uint32_t su = (uint32_t)s, bt = (uint32_t)block_tokens;
   uint32_t blk = su / bt;
-  return gload<int32_t>(reinterpret_cast<const uint8_t*>(page_table + blk)) * block_tokens + (int32_t)(su - blk * bt);
+  return {gload<int32_t>(reinterpret_cast<const uint8_t*>(page_table + blk)), (int32_t)(su - blk * bt)};
 }
+__device__ __forceinline__ int32_t row_of(const RowRef& r, int block_tokens) { return r.entry * block_tokens + r.rest; }
 
 struct HeaderWords {
   uintx4 a, b, c;
@@ -228,7 +235,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
 
   // what one unit loads: the destination row of row i (computed by lane i), the V metadata word of group
   // (row lane / H, head lane % H), and the code words
-  int32_t my_row = 0;
+  RowRef my_ref = {0, 0};
   uint32_t vm = 0;
   bool v_owner = false;
   Codes<BITS> cw[kDecRows][kDecSegs];
@@ -236,8 +243,8 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     {
       int t = t0 + (lane & (kDecRows - 1));
       const int64_t hop = t >= drop.split ? drop.jump : 0;
-      my_row = 0;
-      if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
+      my_ref = RowRef{0, 0};
+      if (t < n) my_ref = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
     }
     if (is_v) {
       int t = t0 + lane / kDecHeads;
@@ -336,6 +343,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
     {
       const bool any_fix = __builtin_amdgcn_ballot_w64(fix) != 0;
       auto param_of = [&](int, int s) { return [&gp, s](int j) -> const GroupParams& { return gp[s][j]; }; };
+      const int32_t my_row = row_of(my_ref, a.block_tokens);
 #pragma unroll
       for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
       if (any_fix) run(t0_wave, Yes{}, param_of); else run(t0_wave, No{}, param_of);
@@ -376,6 +384,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
           if (t0 >= n) return;  // wave-uniform
           load_unit(t0);
         }
+        const int32_t my_row = row_of(my_ref, a.block_tokens);
 #pragma unroll
         for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
         run(t0, fix_tag, param_of);
@@ -394,6 +403,7 @@ __device__ __forceinline__ void decode_unit(const DecodeParams& a, const kvh_ite
         if (t0 >= n) return;  // wave-uniform
         load_unit(t0);
       }
+      const int32_t my_row = row_of(my_ref, a.block_tokens);
 #pragma unroll
       for (int i = 0; i < kDecRows; ++i) rows[i] = __builtin_amdgcn_readlane(my_row, i);
       GroupParams mine = {0.0f, 0.0f, 0u};
@@ -451,11 +461,11 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
   for (int u = 0; u < kDecSub; ++u) {
     const int t0 = t0_wave + u * kDecRows;
     if (t0 >= n) return;  // wave-uniform
-    int32_t my_row = 0;
+    RowRef my_ref = {0, 0};
     {
       int t = t0 + (lane & (kDecRows - 1));
       const int64_t hop = t >= drop.split ? drop.jump : 0;
-      if (t < n) my_row = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
+      if (t < n) my_ref = physical_row(it.dst_token0 + t + hop, it.page_table, a.block_tokens);
     }
     uintx4 d[kDecRows][kDecSegs];
 #pragma unroll
@@ -465,6 +475,7 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
 #pragma unroll
       for (int s = 0; s < kDecSegs; ++s) d[i][s] = gload_stream<uintx4>(rows_in + (size_t)t * geo.row_bytes + ch[s] * 2u);
     }
+    const int32_t my_row = row_of(my_ref, a.block_tokens);
 #pragma unroll
     for (int i = 0; i < kDecRows; ++i) {
       const int32_t r = __builtin_amdgcn_readlane(my_row, i);
