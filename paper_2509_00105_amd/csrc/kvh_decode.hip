@@ -201,7 +201,9 @@ __device__ __forceinline__ bool header_matches(const HeaderWords& h, int dt, int
 
 // One wave's share of a block: kDecSub units of kDecRows consecutive rows each, one after the other.  Every load a
 // unit needs (page-table entries, metadata, codes; for the first unit also the header) is issued up front so that
-// their latencies overlap; the header verdict is taken before anything is stored.  The caller guarantees
+// their latencies overlap; the header verdict is taken before anything is stored.  (The compiler is free to move
+// loads whose results are only needed past the verdict below it, and does so with the code words; keeping them in
+// front of it was measured and changes nothing.)  The caller guarantees
 // kvh_blob_size(l, n_tokens, c, level) readable bytes at the blob pointer, so these loads stay inside the buffer
 // whatever the header says.
 template <int DT, int BITS>
