@@ -205,6 +205,7 @@ struct EncodeParams {
   int64_t jump;
   uint32_t hdr_orig_tokens, hdr_sink, hdr_window;
   int n_inline;  // > 0: the jobs are inline_items[0 .. n_inline), read from the kernel-argument segment
+  int plane_group;  // block order: (layer, K|V) planes that consecutive blocks cycle through (set by the launcher)
   kvh_enc_item inline_items[kInlineItems];
 };
 

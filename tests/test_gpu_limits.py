@@ -110,3 +110,27 @@ def test_one_long_entry_in_a_single_blob(kvh):
     wk, wv = oracle.decode(want, dt, l, n, c, level)
     assert np.array_equal(to_host(ok), wk) and np.array_equal(to_host(ov), wv)
     assert np.array_equal(low.cpu().numpy(), oracle.transcode(oracle.encode(k, v, dt, 1), dt, l, n, c, 1, 2))
+
+
+@pytest.mark.parametrize("l,n_big", [(5, 56000), (9, 32000)])
+def test_planes_far_apart(kvh, l, n_big):
+    """Entries cut out of a tensor whose (layer, K|V) planes lie more than 1 GiB apart in all: the kernels then walk
+    the planes in another block order (the encoder in groups of 8 planes, here one or two full groups and a last
+    group of 2; the decoder plane by plane), which must not change a byte."""
+    dt, n, c, t0 = BF16, 300, 1024, 100
+    k, v = gen.make_kv(l, n, c, dt, seed=100 + l)
+    kbig = torch.zeros((l, n_big, c), dtype=TDT[dt], device="cuda"); vbig = torch.zeros_like(kbig)
+    assert l * kbig.stride(0) * 2 > (1 << 29)
+    kbig[:, t0:t0 + n] = to_dev(k, dt); vbig[:, t0:t0 + n] = to_dev(v, dt)
+    obig_k = torch.zeros_like(kbig); obig_v = torch.zeros_like(vbig)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for level in range(4):
+        want = oracle.encode(k, v, dt, level)
+        blob = kvh.encode(kbig[:, t0:t0 + n], vbig[:, t0:t0 + n], level)
+        kvh.decode(blob, level, n, obig_k, obig_v, dst_token0=t0, status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        assert np.array_equal(blob.cpu().numpy(), want), (l, level)
+        wk, wv = oracle.decode(want, dt, l, n, c, level)
+        assert np.array_equal(to_host(obig_k[:, t0:t0 + n]), wk) and np.array_equal(to_host(obig_v[:, t0:t0 + n]), wv), (l, level)
+    assert not obig_k[:, :t0].any() and not obig_k[:, t0 + n:].any() and not obig_v[:, :t0].any() and not obig_v[:, t0 + n:].any()
