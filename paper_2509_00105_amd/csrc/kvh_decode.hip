@@ -492,10 +492,13 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
 }
 
 // grid = (64-row blocks x spans, 2 * l, items); span fastest; wave w of a block takes rows 8 w .. 8 w + 7 of its 64.
-// Waves per SIMD the register allocation is held to (0 = compiler's choice).  The kernel needs 93 registers, which
-// would let two blocks (16 waves) share a CU; the write stream does better with fewer waves in flight.  Measured on
-// the 8K-token shape, 8 / 4 / 2 bits, % of HBM peak in the benchmark's rotation: 16 waves per CU 68.4 / 71.6 / 71.3,
-// this setting (allocation raised to three waves per SIMD) 70.4 / 73.8 / 74.5, two waves per SIMD 71.0 / 69.2 / 67.1.
+// Waves per SIMD the register allocation is held to (0 = compiler's choice).  The kernel needs about 100 registers,
+// which would let two blocks (16 waves) share a CU; the write stream does better with fewer waves in flight.  Measured
+// on the 8K-token shape with plain non-temporal stores, 8 / 4 / 2 bits, % of HBM peak in the benchmark's rotation:
+// 16 waves per CU 68.4 / 71.6 / 71.3, this setting (allocation raised to three waves per SIMD, one block per CU)
+// 70.4 / 73.8 / 74.5, two waves per SIMD 71.0 / 69.2 / 67.1; with the device-scope stores of the 8- and 4-bit levels
+// the order is the same (16 waves per CU 70.6 / 73.6 / 72.8, this setting 73.0 / 70.9 / 69.3 before each level had its
+// own store and parameter form, two waves per SIMD 71.7 / 68.5 / 66.2).
 #ifndef KVH_DEC_WPE
 #define KVH_DEC_WPE 3
 #endif
