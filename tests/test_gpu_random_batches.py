@@ -29,7 +29,7 @@ def host_bits(t):
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", range(28))
 def test_random_batches(kvh, case):
     rng = np.random.default_rng(77000 + case)
     dt = int(rng.integers(0, 2))

@@ -35,7 +35,7 @@ def host_bits(t):
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(40))
 def test_random_geometry(kvh, case):
     rng = np.random.default_rng(1000 + case)
     dt = int(rng.integers(0, 2))
