@@ -248,3 +248,62 @@ def test_transcode_from_8_bits_away_from_zero(kvh, mix, dt):
         torch.cuda.synchronize()
         assert status.item() == 0
         assert_same_blob(got.cpu().numpy(), want, "8 -> %d, %s" % (kvh.level_bits(lo), mix))
+
+
+def four_bit_blob_with_every_code(l, n, c, dt, far, seed):
+    """A 4-bit blob whose groups hold all sixteen codes: the encoder's metadata for the given kind of data (near zero,
+    or 20 to 60 ranges away from it), the code sections refilled at random, with code 0 and code 15 planted in every
+    group so that the stored minimum and maximum remain the group's own."""
+    rng = np.random.default_rng(seed)
+    sig = np.exp(0.5 * rng.standard_normal((l, 1, c))).astype(np.float32)
+    kf = rng.standard_normal((l, n, c)).astype(np.float32) * sig
+    vf = rng.standard_normal((l, n, c)).astype(np.float32)
+    if far:
+        kf += (rng.choice([-1.0, 1.0], (l, 1, c)) * rng.uniform(20, 60, (l, 1, c))).astype(np.float32) * 6 * sig
+        vf += (rng.choice([-1.0, 1.0], (l, n, 1)) * rng.uniform(20, 60, (l, n, 1))).astype(np.float32) * 6
+    kf[:, :, 5::64] = 3.25                                   # constant channels: degenerate K groups
+    vf[:, 7::50, 128:256] = -1.5                             # and degenerate V groups
+    src = oracle.encode(gen._cast_to_bits(kf, dt), gen._cast_to_bits(vf, dt), dt, 1).copy()
+    for lam in range(l):
+        off = oracle.section_offsets(l, n, c, 1, lam)
+        kc = rng.integers(0, 256, (n, c // 2), dtype=np.uint8)
+        kc[0::128] = 0x00                                    # first row of every token-group: code 0 in every channel
+        kc[1::128] = 0xFF                                    # second row: code 15
+        vc = rng.integers(0, 256, (n, c // 2), dtype=np.uint8)
+        vc[:, 0::64] = 0xF0                                  # first two channels of every head: codes 0 and 15
+        src[off["kcodes"]:off["kcodes"] + n * c // 2] = kc.reshape(-1)
+        src[off["vcodes"]:off["vcodes"] + n * c // 2] = vc.reshape(-1)
+    return src
+
+
+@pytest.mark.parametrize("dt", [F16, BF16])
+@pytest.mark.parametrize("far", [False, True])
+def test_transcode_4_to_2_tables(kvh, far, dt):
+    """4 -> 2 goes through a 16-entry table per group.  Groups near zero have the table of exact arithmetic (steps at
+    3, 8, 13); groups far from zero compared with their range have their steps moved by the rounding to the 16-bit
+    type, so no shortcut may assume the usual table.  Both, with degenerate groups among them and a partial last span
+    (lanes without a group), on blobs that hold every code in every group, must equal the oracle."""
+    l, n, c = 2, 300, 1152
+    assert n > 257 and n % 128 > 1                           # every token-group has its two planted rows
+    src = four_bit_blob_with_every_code(l, n, c, dt, far, 177 + dt + 10 * far)
+    # the premise, checked with the oracle on the K groups of the first layer's first token-group
+    wk, _ = oracle.decode(src, dt, l, n, c, 1)
+    two = oracle.encode(wk, wk, dt, 2)
+    off1 = oracle.section_offsets(l, n, c, 1, 0); off2 = oracle.section_offsets(l, n, c, 2, 0)
+    raw4 = src[off1["kcodes"]:off1["kcodes"] + 128 * c // 2].reshape(128, c // 2)
+    q4 = np.stack([raw4 & 15, raw4 >> 4], axis=2).reshape(128, c).astype(np.int64)
+    raw2 = two[off2["kcodes"]:off2["kcodes"] + 128 * c // 4].reshape(128, c // 4)
+    q2 = np.stack([(raw2 >> (2 * i)) & 3 for i in range(4)], axis=2).reshape(128, c)
+    live = (q2 != 0).any(axis=0)                             # a degenerate group maps every code to 0
+    moved = ((np.digitize(q4, [3, 8, 13]) != q2) & live[None, :]).any(axis=0)
+    assert live.mean() > 0.9
+    if far and dt == BF16:
+        assert moved.mean() > 0.02
+    if not far:
+        assert not moved.any()
+    want = oracle.transcode(src, dt, l, n, c, 1, 2)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = kvh.transcode(torch.from_numpy(src).cuda(), dt, l, n, c, 1, 2, status=status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    assert_same_blob(got.cpu().numpy(), want, "4 -> 2, far=%s" % far)
