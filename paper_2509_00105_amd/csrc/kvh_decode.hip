@@ -6,11 +6,13 @@
 // 1024-channel span (two 512-channel segments), i.e. 16 KiB of contiguous output when c = 1024.
 // A lane owns 8 channels per segment, so each store is one 128-bit access and the wave writes
 // 1 KiB of a row per instruction.  A block is 8 such units: 64 consecutive rows of one span, which
-// always lie in one K token-group.  K metadata (per channel) is therefore turned into fp32
-// parameters once per block, two channels per thread, and handed to the waves through 12 KiB of
-// LDS; V metadata (per token and head) is prepared by one lane per group and broadcast inside the
-// wave, and V blocks never meet at a barrier.  The rare groups whose top code does not land
-// exactly on the stored maximum select a slower row loop through a uniform branch.
+// always lie in one K token-group.  K metadata (per channel) is turned into fp32 parameters either
+// once per block, two channels per thread, and handed to the waves through 12 KiB of LDS (8 bits),
+// or by every wave for the channels of its own lanes, with no barrier (4 and 2 bits); V metadata
+// (per token and head) is prepared by one lane per group and broadcast inside the wave, and V blocks
+// never meet at a barrier.  The rare groups whose top code does not land exactly on the stored
+// maximum select a slower row loop through a uniform branch.  Stores are non-temporal, at 8 and 4
+// bits also device-scoped; which form each level takes is measured, see kStoreThrough and kOwnK.
 #include <type_traits>
 
 #include "kvh_common.hpp"
