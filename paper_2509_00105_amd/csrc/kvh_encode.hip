@@ -605,13 +605,17 @@ int launch_encode(const EncodeParams& a, int dt, int n_items, int max_tokens, hi
   dim3 grid((unsigned)(tiles * nstrips), (unsigned)(2 * a.l), (unsigned)n_items);
   EncodeParams b = a;
   b.max_tokens = max_tokens;
-  // All planes in one group while the source planes of the call lie within 1 GiB of each other; groups of 8 (with
-  // the dispatcher dealing consecutive blocks to the 8 XCDs in turn, every XCD then streams through one plane at
-  // a time) beyond that.  Measured at 8 / 4 / 2 bits, % of HBM peak, one group / groups of 8: 32 x 8192 tokens
-  // 71.4 / 76.3 / 74.5 against 69.9 / 74.3 / 73.5; 80 x 32768 tokens 74.7 / 72.0 / 67.4 against 76.0 / 76.2 / 73.2;
-  // 32 x 131072 tokens 77.3 / 71.5 / 68.2 against 77.6 / 73.2 / 70.5; 80 x 8192 tokens 73.3 / 73.0 / 70.8 against
-  // 74.4 / 76.6 / 76.4; groups of 16 like groups of 8, groups of 4 and of 32 worse.
-  b.plane_group = (int64_t)a.l * a.layer_stride * 2 <= ((int64_t)1 << 29) ? 2 * a.l : 8;
+  // Plane group.  With the dispatcher dealing consecutive blocks to the 8 XCDs in turn, groups of 8 make every XCD
+  // stream through one plane at a time; that is the default.  Long items do better with the two planes of a layer
+  // alone (their sections of a blob are megabytes apart, and fewer planes at a time keep the writes together), and
+  // short items of a source within 1 GiB with all planes in one group.  Measured at 8 / 4 / 2 bits, % of HBM peak:
+  //   80 x 32768 tokens in 512-token items, all planes / groups of 8:  74.7 / 72.0 / 67.4   76.0 / 76.2 / 73.2
+  //   32 x 8192 tokens in 256-token items (the benchmark's rotation):   71.4 / 76.3 / 74.5   69.9 / 74.3 / 73.5
+  //   32 x 8192 tokens in one item, all / 8 / 2 (the kernel alone):     72.6 / 66.0 / 64.0   73.3 / 73.4 / 70.3   74.4 / 73.8 / 74.7
+  //   32 x 32768 tokens in one item, all / 8 / 2:                       75.0 / 61.3 / 67.9   76.1 / 73.9 / 71.2   75.2 / 75.5 / 75.5
+  //   32 x 32768 tokens in 2048-token items, all / 8 / 2:               74.7 / 75.5 / 69.3   75.5 / 77.5 / 78.0   74.3 / 76.5 / 75.9
+  const bool near = (int64_t)a.l * a.layer_stride * 2 <= ((int64_t)1 << 29);
+  b.plane_group = max_tokens >= 8192 ? 2 : near && max_tokens <= 512 ? 2 * a.l : 8;
   if (dt == KVH_F16)
     launch_kernel(encode_kernel<KVH_F16>, grid, dim3(kEncThreads), 0u, stream, b);
   else

@@ -134,3 +134,21 @@ def test_planes_far_apart(kvh, l, n_big):
         wk, wv = oracle.decode(want, dt, l, n, c, level)
         assert np.array_equal(to_host(obig_k[:, t0:t0 + n]), wk) and np.array_equal(to_host(obig_v[:, t0:t0 + n]), wv), (l, level)
     assert not obig_k[:, :t0].any() and not obig_k[:, t0 + n:].any() and not obig_v[:, :t0].any() and not obig_v[:, t0 + n:].any()
+
+
+def test_long_entry_over_several_layers(kvh):
+    """More than 8,192 tokens in one blob of several layers: the encoder then walks the planes two at a time."""
+    dt, l, n, c = F16, 3, 8200, 256
+    k, v = gen.make_kv(l, n, c, dt, seed=8)
+    kd, vd = to_dev(k, dt), to_dev(v, dt)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for level in range(4):
+        want = oracle.encode(k, v, dt, level)
+        blob = kvh.encode(kd, vd, level)
+        ok = torch.zeros((l, n, c), dtype=TDT[dt], device="cuda"); ov = torch.zeros_like(ok)
+        kvh.decode(blob, level, n, ok, ov, status=status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        assert np.array_equal(blob.cpu().numpy(), want), level
+        wk, wv = oracle.decode(want, dt, l, n, c, level)
+        assert np.array_equal(to_host(ok), wk) and np.array_equal(to_host(ov), wv), level
