@@ -180,7 +180,7 @@ struct DecodeParams {
   int32_t* status;                     // nullable; indexed by item
   int l, c, block_tokens;
   int max_tokens;  // rows the grid covers per item: an item with more tokens is refused on the device
-  int planes_first;  // block order chosen by the launcher (see decode_kernel)
+  int row_tile;  // block order chosen by the launcher: blocks of a plane that are taken before the next plane (see decode_kernel)
   // Token-dropped entries (single-item calls only): token t >= split lands `jump` rows further on,
   // and the header must carry these three words (all zero for an ordinary blob).
   int32_t split;

@@ -512,13 +512,21 @@ __device__ __forceinline__ void decode_raw_unit(const DecodeParams& a, const kvh
 template <int DT>
 __global__ __launch_bounds__(kDecThreads) KVH_DEC_OCC void decode_kernel(DecodeParams a) {
   const int item_idx = blockIdx.z;
-  // Block order.  Planes first (consecutive blocks of the dispatch order take the same rows of consecutive
-  // (layer, K|V) planes) when the launcher found all planes of the call within 1 GiB, rows first otherwise.
-  int lay_kv = blockIdx.y, bx = blockIdx.x;
-  if (a.planes_first) {
+  // Block order: `row_tile` consecutive 64-row blocks of a plane, then the same rows of the next (layer, K|V)
+  // plane, and so on through all planes, then the next tile of rows (the last tile may be smaller).  1 walks the
+  // planes first, anything from the number of blocks per plane upwards walks plane by plane.
+  int lay_kv, bx;
+  {
     const int lin_xy = blockIdx.y * gridDim.x + blockIdx.x;
-    lay_kv = lin_xy % gridDim.y;
-    bx = lin_xy / gridDim.y;
+    const int per_plane = gridDim.x, planes = gridDim.y;
+    const int rt = a.row_tile < 1 ? 1 : a.row_tile < per_plane ? a.row_tile : per_plane;
+    const int full = per_plane / rt;
+    const int tile = lin_xy / (rt * planes);
+    const int first = (tile < full ? tile : full) * rt;          // first block (within a plane) of this tile
+    const int size = tile < full ? rt : per_plane - full * rt;   // blocks per plane in it
+    const int j = lin_xy - first * planes;
+    lay_kv = j / size;
+    bx = first + j % size;
   }
   kvh_item it;
   DropInfo drop = {kNoSplit, 0, 0u, 0u, 0u};  // ordinary batch items are never token-dropped
@@ -606,9 +614,16 @@ int launch_decode(const DecodeParams& a, int dt, int n_items, int max_tokens, hi
   dim3 grid(gx, (unsigned)(2 * a.l), (unsigned)n_items);
   DecodeParams b = a;
   b.max_tokens = max_tokens;
-  // Measured on the 8K / 32K / 128K-token shapes: walking the planes first is worth about 1 % when the destination
-  // planes of the call lie within 1 GiB of each other and costs 3-4 % when they span 4 GiB or more.
-  b.planes_first = (int64_t)a.l * a.layer_stride * 2 <= ((int64_t)1 << 29) ? 1 : 0;
+  // Row tile.  Destination planes within 1 GiB of each other: planes first (one block per plane and turn), worth
+  // 1-2 % there over anything longer.  Beyond that: four blocks (256 rows) per plane and turn for items of up to
+  // 8,192 tokens, plane by plane for longer ones.  Measured on ten tensors of 2.5 to 16 GiB (8 to 80 layers, 8K to
+  // 128K tokens) against walking plane by plane, the kernel alone, 8 / 4 / 2 bits in points of HBM peak: items of 512
+  // tokens -1.4 to +3.9 / -1.6 to +5.3 / -0.4 to +4.9, of 1,024 tokens +0.9 to +8.9 / +1.0 to +11.8 / +2.2 to +9.2
+  // (walking plane by plane has a hole there, 67-69 % on most tensors), of 4,096 tokens -1.8 to +5.1 / -1.0 to +6.9 /
+  // -3.6 to +6.2; one item of 16,384 tokens +0.8 to +4.3 / -6.3 to +1.0 / -3.4 to +1.1, hence the limit.  Tiles of
+  // 2 are a point below tiles of 4, tiles of 8 two to four, tiles of 16 are the hole again.
+  const bool near = (int64_t)a.l * a.layer_stride * 2 <= ((int64_t)1 << 29);
+  b.row_tile = near ? 1 : max_tokens <= 8192 ? 4 : 0x7fffffff;
   if (dt == KVH_F16)
     launch_kernel(decode_kernel<KVH_F16>, grid, dim3(kDecThreads), 0u, stream, b);
   else

@@ -540,7 +540,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4, 
   {
     const int lin_xy = blockIdx.y * gridDim.x + blockIdx.x;
     const int planes = gridDim.y, per_plane = gridDim.x;
-    const int group = a.plane_group < planes ? a.plane_group : planes;
+    const int group = a.plane_group < 1 ? 1 : a.plane_group < planes ? a.plane_group : planes;
     const int full = planes / group;
     const int g = lin_xy / (group * per_plane);
     const int first = (g < full ? g : full) * group;            // first plane of this block's group
